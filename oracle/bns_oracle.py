@@ -1,0 +1,233 @@
+"""CPU oracle for one partition's BNS-GCN training step  --  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import
+this module; the product path never does.  It is independent of the HIP
+library (no shared code) and works in fp64.
+
+What it computes, and where the paper defines it:
+
+* ``sample``       Algorithm 1, selection step: keep each boundary node
+                   independently with probability p (redrawn every epoch).
+* ``induced_csr``  Algorithm 1, subgraph step: node-induced subgraph on the
+                   inner nodes plus the kept boundary nodes.
+* ``forward``      Eq. 1 (aggregate) then Eq. 2 (update) per layer, in the
+                   sampled matrix form of Appendix A:
+                   Z = [P_VV P_VU] S [H_V ; H_U] W with the full-graph
+                   propagation matrix P = D~^-1/2 (A+I) D~^-1/2 and
+                   S = diag(1 for inner, 1/p for kept boundary); ReLU between
+                   layers, none after the last.
+* ``loss_and_grad``Algorithm 1, loss step: sum over inner nodes.
+* ``backward``     Algorithm 1, backward step: gradients of that sum with
+                   respect to every weight matrix, plus the gradients of the
+                   kept boundary features (what would be sent back to their
+                   owners, Section 3.2).
+* ``step``         one iteration of Algorithm 1 for one partition, without the
+                   exchange steps (one partition only) and with optional SGD.
+
+The heavy integer and sparse loops are plain C (``bns_oracle.c``); dense
+products use numpy's fp64 matmul as a library primitive.
+
+Pins (tests/test_oracle_*.py): Philox known-answer vectors; binomial keep
+statistics; p = 1 / p = 0 special cases; dense brute-force forward and
+backward; fp64 finite differences; multi-partition emulation against the
+dense full-graph GCN; unbiasedness and the closed-form variance of Appendix A.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libbns_oracle.so")
+_lib = None
+
+_i32p = np.ctypeslib.ndpointer(dtype=np.int32, flags="C_CONTIGUOUS")
+_i64p = np.ctypeslib.ndpointer(dtype=np.int64, flags="C_CONTIGUOUS")
+_f64p = np.ctypeslib.ndpointer(dtype=np.float64, flags="C_CONTIGUOUS")
+_f32p = np.ctypeslib.ndpointer(dtype=np.float32, flags="C_CONTIGUOUS")
+_u32p = np.ctypeslib.ndpointer(dtype=np.uint32, flags="C_CONTIGUOUS")
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            from . import build as _b
+            _b.build(force=False)
+        L = C.CDLL(_LIB_PATH)
+        L.bnso_num_threads.restype = C.c_int
+        L.bnso_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
+        L.bnso_draw.restype = C.c_uint32
+        L.bnso_draw.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint64]
+        L.bnso_threshold.restype = C.c_uint64
+        L.bnso_threshold.argtypes = [C.c_double]
+        L.bnso_sample.restype = C.c_int64
+        L.bnso_sample.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_double, _i64p, C.c_int64,
+                                  _i32p, _i32p]
+        L.bnso_induced_csr.restype = C.c_int64
+        L.bnso_induced_csr.argtypes = [C.c_int64, _i32p, _i32p, _i32p, _i32p, _i32p]
+        L.bnso_transpose.argtypes = [C.c_int64, C.c_int64, _i32p, _i32p, _i32p, _i32p]
+        L.bnso_aggregate.argtypes = [C.c_int64, C.c_int64, _i32p, _i32p, _i32p, _i32p, _i32p,
+                                     C.c_double, _f64p, _f32p, _f64p]
+        L.bnso_aggregate_bwd.argtypes = [C.c_int64, C.c_int64, C.c_int64, _i32p, _i32p, _i32p, _i32p,
+                                         _i32p, C.c_double, _f64p, _f64p, _f64p]
+        _lib = L
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().bnso_num_threads())
+
+
+def philox4x32_10(ctr, key):
+    out = np.zeros(4, dtype=np.uint32)
+    lib().bnso_philox4x32_10(np.asarray(ctr, dtype=np.uint32), np.asarray(key, dtype=np.uint32), out)
+    return out
+
+
+def draw(seed: int, epoch: int, part_id: int, gid: int) -> int:
+    return int(lib().bnso_draw(seed, epoch, part_id, gid))
+
+
+def threshold(p: float) -> int:
+    return int(lib().bnso_threshold(float(p)))
+
+
+def sample(seed, epoch, part_id, p, halo_gid):
+    """-> (kept_ids int32[n_u] ascending, remap int32[B] rank-or-minus-one)."""
+    halo_gid = np.ascontiguousarray(halo_gid, dtype=np.int64)
+    B = halo_gid.shape[0]
+    kept = np.empty(max(B, 1), dtype=np.int32)
+    remap = np.empty(max(B, 1), dtype=np.int32)
+    n = lib().bnso_sample(seed, epoch, part_id, float(p), halo_gid, B, kept, remap)
+    return kept[:n].copy(), remap[:B]
+
+
+def induced_csr(n_in, row_ptr0, col0, remap):
+    """-> (row_ptr int32[n_in+1], col_idx int32[nnz]) of the sampled subgraph."""
+    row_ptr = np.empty(n_in + 1, dtype=np.int32)
+    col_idx = np.empty(max(col0.shape[0], 1), dtype=np.int32)
+    remap_c = np.ascontiguousarray(remap if remap.shape[0] else np.zeros(1, np.int32))
+    nnz = lib().bnso_induced_csr(n_in, row_ptr0, col0, remap_c, row_ptr, col_idx)
+    return row_ptr, col_idx[:nnz].copy()
+
+
+def transpose(n_rows, n_cols, row_ptr, col_idx):
+    t_ptr = np.empty(n_cols + 1, dtype=np.int32)
+    t_col = np.empty(max(col_idx.shape[0], 1), dtype=np.int32)
+    ci = np.ascontiguousarray(col_idx if col_idx.shape[0] else np.zeros(1, np.int32))
+    lib().bnso_transpose(n_rows, n_cols, row_ptr, ci, t_ptr, t_col)
+    return t_ptr, t_col[:col_idx.shape[0]].copy()
+
+
+def _pad1(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a if a.size else np.zeros(1, dtype=dtype)
+
+
+def aggregate(part, row_ptr, col_idx, kept_ids, s_halo, H_in, halo_h):
+    """Eq. 1 in the sampled form of Appendix A -> A f64[n_in, d]."""
+    n_in, d = H_in.shape
+    A = np.empty((n_in, d), dtype=np.float64)
+    lib().bnso_aggregate(n_in, d, row_ptr, _pad1(col_idx, np.int32), part.deg_in,
+                         _pad1(part.deg_halo, np.int32), _pad1(kept_ids, np.int32), float(s_halo),
+                         np.ascontiguousarray(H_in, dtype=np.float64),
+                         _pad1(halo_h, np.float32), A)
+    return A
+
+
+def aggregate_bwd(part, t_row_ptr, t_col_idx, kept_ids, s_halo, dA):
+    """dHcat = S^T P^T dA -> (dH_in f64[n_in, d], dhalo f64[n_u, d])."""
+    n_in, d = dA.shape
+    n_u = kept_ids.shape[0]
+    dH = np.empty((n_in, d), dtype=np.float64)
+    dhalo = np.empty((max(n_u, 1), d), dtype=np.float64)
+    lib().bnso_aggregate_bwd(n_in, n_u, d, t_row_ptr, _pad1(t_col_idx, np.int32), part.deg_in,
+                             _pad1(part.deg_halo, np.int32), _pad1(kept_ids, np.int32),
+                             float(s_halo), np.ascontiguousarray(dA, dtype=np.float64), dH, dhalo)
+    return dH, dhalo[:n_u]
+
+
+def halo_scale(p: float, n_kept: int) -> float:
+    """S_uu for kept boundary nodes (Appendix A).  Never formed when nothing is kept (p = 0)."""
+    return 1.0 / p if n_kept > 0 else 1.0
+
+
+def forward(part, sub, X, halo_h, W, p):
+    """All layers.  ``sub`` = dict(row_ptr, col_idx, kept_ids).  -> (A list, H list) with
+    H[0] = X, H[l] = ReLU(A[l] W[l]) for l < L and H[L] = A[L] W[L] (logits)."""
+    L = len(W)
+    s = halo_scale(p, sub["kept_ids"].shape[0])
+    H = [np.asarray(X, dtype=np.float64)]
+    A = [None]
+    for l in range(1, L + 1):
+        a = aggregate(part, sub["row_ptr"], sub["col_idx"], sub["kept_ids"], s, H[l - 1], halo_h[l - 1])
+        z = a @ np.asarray(W[l - 1], dtype=np.float64)
+        A.append(a)
+        H.append(np.maximum(z, 0.0) if l < L else z)
+    return A, H
+
+
+def loss_and_grad(logits, labels, loss_kind):
+    """Sum over inner nodes of the per-node loss (Algorithm 1) and its gradient.
+
+    kind 0: softmax cross-entropy, labels int[n];  kind 1: sigmoid binary
+    cross-entropy summed over labels, labels {0,1}[n, C].
+    """
+    z = np.asarray(logits, dtype=np.float64)
+    if loss_kind == 0:
+        m = z.max(axis=1, keepdims=True)
+        e = np.exp(z - m)
+        se = e.sum(axis=1, keepdims=True)
+        lse = (m + np.log(se))[:, 0]
+        idx = np.arange(z.shape[0])
+        loss = float(np.sum(lse - z[idx, labels]))
+        g = e / se
+        g[idx, labels] -= 1.0
+        return loss, g
+    y = np.asarray(labels, dtype=np.float64)
+    loss = float(np.sum(np.maximum(z, 0.0) - z * y + np.log1p(np.exp(-np.abs(z)))))
+    e = np.exp(-np.abs(z))
+    g = np.where(z >= 0, 1.0 / (1.0 + e), e / (1.0 + e)) - y
+    return loss, g
+
+
+def backward(part, sub, A, H, W, dZ_last, p):
+    """-> (dW list[L], dhalo list[L] (entry 0 is None), dH list: dH[l] = grad wrt H[l], l=1..L-1)."""
+    L = len(W)
+    s = halo_scale(p, sub["kept_ids"].shape[0])
+    dW = [None] * L
+    dhalo = [None] * L
+    dH = [None] * (L + 1)
+    dZ = dZ_last
+    for l in range(L, 0, -1):
+        if l < L:
+            dZ = dH[l] * (H[l] > 0.0)
+        dW[l - 1] = A[l].T @ dZ
+        if l > 1:
+            dA = dZ @ np.asarray(W[l - 1], dtype=np.float64).T
+            dH[l - 1], dhalo[l - 1] = aggregate_bwd(part, sub["t_row_ptr"], sub["t_col_idx"],
+                                                    sub["kept_ids"], s, dA)
+    return dW, dhalo, dH
+
+
+def sample_and_build(part, seed, epoch, p):
+    kept_ids, remap = sample(seed, epoch, part.part_id, p, part.halo_gid)
+    row_ptr, col_idx = induced_csr(part.n_in, part.row_ptr0, part.col0, remap)
+    t_row_ptr, t_col_idx = transpose(part.n_in, part.n_in + kept_ids.shape[0], row_ptr, col_idx)
+    return dict(kept_ids=kept_ids, remap=remap, row_ptr=row_ptr, col_idx=col_idx,
+                t_row_ptr=t_row_ptr, t_col_idx=t_col_idx)
+
+
+def step(part, loss_kind, X, halo_h, labels, W, seed, epoch, p, lr=0.0):
+    """One iteration of Algorithm 1 on one partition (no exchange, optional SGD)."""
+    sub = sample_and_build(part, seed, epoch, p)
+    A, H = forward(part, sub, X, halo_h, W, p)
+    loss, dZ = loss_and_grad(H[-1], labels, loss_kind)
+    dW, dhalo, dH = backward(part, sub, A, H, W, dZ, p)
+    out = dict(sub=sub, A=A, H=H, loss=loss, dZ_last=dZ, dW=dW, dhalo=dhalo, dH=dH)
+    if lr > 0.0:
+        out["W_new"] = [np.asarray(w, dtype=np.float64) - lr * g for w, g in zip(W, dW)]
+    return out
