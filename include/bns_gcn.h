@@ -1,0 +1,170 @@
+/*
+ * bns_gcn.h -- C ABI of the MI355X (gfx950) BNS-GCN partition step.
+ *
+ * One partition's full-graph GCN training iteration with random boundary-node
+ * sampling (Algorithm 1, per-partition view), without the exchange steps: the
+ * features of boundary nodes are supplied by the caller as preloaded buffers,
+ * one per layer, standing in for what the other partitions would send.
+ *
+ * Conventions
+ *  - "dev" pointers are device (HBM) pointers owned by the caller; "host"
+ *    pointers are ordinary host memory.  The library never allocates or frees
+ *    device memory: everything it needs lives in the caller's workspace.
+ *  - All matrices are dense row-major fp32 without padding.
+ *  - `stream` is a hipStream_t passed as void*.  Every call validates its
+ *    arguments on the host, enqueues its kernels on `stream` and returns; it
+ *    does not synchronise (bns_create is the one exception).  Counts produced
+ *    on the device (|U|, nnz) stay on the device.
+ *  - Every function returns a bns_status; nothing throws or aborts.  After a
+ *    failure bns_last_error(ctx) describes it.
+ *  - Calls on one context must be issued on one stream at a time: they share
+ *    the workspace.
+ *
+ * Layout of a partition (Section 3.1: inner node set V_i, boundary node set B_i)
+ *  - inner nodes have local ids 0..n_in-1; boundary node b (0..n_halo-1)
+ *    appears as column n_in+b.  Only inner rows exist.
+ *  - row_ptr0/col0: CSR of the local graph incl. one self-loop per row, columns
+ *    strictly ascending in a row (so boundary columns form the row's tail).
+ *  - t_in_ptr/t_in_col: CSR of the transpose of the inner-inner block.
+ *  - halo_ptr/halo_col: for boundary node b, the ascending list of inner rows
+ *    that contain column n_in+b.
+ *  - deg_in/deg_halo: FULL-GRAPH degree + 1 (the diagonal of D~ in Appendix A),
+ *    static over epochs; the normalisation never uses sampled degrees.
+ */
+#ifndef BNS_GCN_H
+#define BNS_GCN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bns_ctx bns_ctx; /* opaque; host-side; holds descriptors and workspace offsets */
+
+typedef enum {
+  BNS_OK = 0,
+  BNS_EINVAL = 1,     /* null pointer, bad size, p outside [0,1] or NaN, bad layer index      */
+  BNS_EOVERFLOW = 2,  /* an index range does not fit int32                                    */
+  BNS_EWORKSPACE = 3, /* workspace too small or misaligned                                    */
+  BNS_EHIP = 4        /* a HIP call or kernel launch failed                                   */
+} bns_status;
+
+typedef struct {
+  int32_t part_id;          /* i: enters the random draw, partitions sample independently */
+  int32_t n_in;             /* |V_i|                                                      */
+  int32_t n_halo;           /* |B_i|  (0 is legal)                                        */
+  int64_t nnz0;             /* entries of col0   = e_in + e_bd                            */
+  int64_t e_in;             /* entries of t_in_col (inner-inner block incl. self-loops)   */
+  int64_t e_bd;             /* entries of halo_col (inner-boundary block)                 */
+  const int32_t *row_ptr0;  /* dev int32[n_in+1]                                          */
+  const int32_t *col0;      /* dev int32[nnz0]                                            */
+  const int32_t *t_in_ptr;  /* dev int32[n_in+1]                                          */
+  const int32_t *t_in_col;  /* dev int32[e_in]                                            */
+  const int32_t *halo_ptr;  /* dev int32[n_halo+1]                                        */
+  const int32_t *halo_col;  /* dev int32[e_bd]                                            */
+  const int64_t *halo_gid;  /* dev int64[n_halo]  global node id of each boundary node    */
+  const int32_t *deg_in;    /* dev int32[n_in]    full-graph degree + 1                   */
+  const int32_t *deg_halo;  /* dev int32[n_halo]  full-graph degree + 1                   */
+} bns_partition_desc;
+
+typedef struct {
+  int32_t n_layers;     /* L >= 1                                                          */
+  const int32_t *dims;  /* host int32[L+1]: d_0 .. d_L (layer l maps d_{l-1} -> d_l)       */
+  int32_t loss_kind;    /* 0: softmax cross-entropy, labels dev int32[n_in]
+                           1: sigmoid binary cross-entropy, labels dev uint8[n_in*d_L]     */
+} bns_model_desc;
+
+/* Bytes of device workspace bns_create needs for this partition and model (sized for p = 1).
+ * Returns 0 if a descriptor is invalid. */
+size_t bns_workspace_bytes(const bns_partition_desc *part, const bns_model_desc *model);
+
+/* Creates a context on the current device.  `dev_ws` (256-byte aligned, >= bns_workspace_bytes)
+ * must stay valid, like every array named in `part`, until bns_destroy.  Runs the one-off
+ * set-up kernels (d~^-1/2, inner/boundary split of the CSR) on `stream` and waits for them. */
+bns_status bns_create(bns_ctx **out, const bns_partition_desc *part, const bns_model_desc *model,
+                      void *dev_ws, size_t ws_bytes, void *stream);
+void bns_destroy(bns_ctx *ctx);
+const char *bns_last_error(const bns_ctx *ctx); /* never NULL; "" if no error so far */
+
+/* Algorithm 1, selection step: U_i <- each b in B_i kept independently with probability p.
+ * keep(b) <=> draw(seed, epoch, part_id, halo_gid[b]) < floor(p * 2^32), where draw is the
+ * first output word of Philox-4x32-10 with counter (gid low, gid high, epoch, part_id) and key
+ * (seed low, seed high): the same (seed, epoch, partition, node) always gives the same decision,
+ * on any machine.  p = 1 keeps all, p = 0 none.
+ *   kept_ids dev int32[n_halo] (capacity): the kept b, ascending, first *n_kept entries valid
+ *   remap    dev int32[n_halo]: rank of b in kept_ids, or -1
+ *   n_kept   dev int32[1]
+ * The context remembers these three pointers for the calls below: the arrays must stay
+ * allocated until a later bns_sample_boundary / bns_train_step replaces them. */
+bns_status bns_sample_boundary(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
+                               int32_t *kept_ids, int32_t *remap, int32_t *n_kept, void *stream);
+
+/* Algorithm 1, subgraph step: the node-induced subgraph on V_i u U_i, in canonical CSR form, and
+ * its transpose for the backward pass.  Uses the sample of the latest bns_sample_boundary.
+ *   row_ptr   dev int32[n_in+1], col_idx dev int32[nnz0] (capacity): inner columns unchanged,
+ *             kept boundary column n_in+b renumbered n_in+remap[b], order preserved
+ *   t_row_ptr dev int32[n_in+n_halo+1] (first n_in+*n_kept+1 valid), t_col_idx dev int32[nnz0]:
+ *             for stacked column u the ascending inner rows holding u
+ *   nnz       dev int32[1]
+ * The context remembers the four array pointers for the layer calls: the arrays must stay
+ * allocated until a later bns_build_sampled_csr / bns_train_step replaces them. */
+bns_status bns_build_sampled_csr(bns_ctx *ctx, int32_t *row_ptr, int32_t *col_idx,
+                                 int32_t *t_row_ptr, int32_t *t_col_idx, int32_t *nnz,
+                                 void *stream);
+
+/* One layer forward, Eq. 1 then Eq. 2 in the sampled matrix form of Appendix A:
+ *   A = [P_VV P_VU] S [H_in ; halo_h[kept_ids]],  S = diag(1 .. 1, 1/p .. 1/p),
+ *   P_vu = (d~_v d~_u)^-1/2;   H_out = A W, followed by ReLU iff relu != 0.
+ * layer in 1..L selects d_in = d_{layer-1}, d_out = d_layer.  Uses the latest sample and CSR.
+ *   H_in dev f32[n_in*d_in]; halo_h dev f32[n_halo*d_in] (ALL boundary rows, unscaled; only
+ *   kept rows are read; may be NULL iff n_halo == 0); W dev f32[d_in*d_out];
+ *   A_saved dev f32[n_in*d_in] (out, kept for backward); H_out dev f32[n_in*d_out] (out). */
+bns_status bns_gcn_layer_fwd(bns_ctx *ctx, int32_t layer, double p, const float *H_in,
+                             const float *halo_h, const float *W, float *A_saved, float *H_out,
+                             int32_t relu, void *stream);
+
+/* One layer backward (Algorithm 1, backward step; Section 3.2: a partition returns feature
+ * gradients of its selected boundary nodes).  With dZ = dH_out (.) [H_out > 0] (or dZ = dH_out
+ * when H_out is NULL, i.e. no ReLU on this layer):
+ *   dW = A_saved^T dZ;  dA = dZ W^T;  [dH_in ; dhalo] = S^T P^T dA.
+ *   dW dev f32[d_in*d_out] (out); dH_in dev f32[n_in*d_in] (out, or NULL to skip dA and the
+ *   transposed aggregate, as for layer 1); dhalo dev f32[n_halo*d_in] (capacity; first *n_kept
+ *   rows valid: gradient w.r.t. the unscaled features of the kept boundary nodes; NULL to skip). */
+bns_status bns_gcn_layer_bwd(bns_ctx *ctx, int32_t layer, double p, const float *dH_out,
+                             const float *H_out, const float *A_saved, const float *W, float *dW,
+                             float *dH_in, float *dhalo, void *stream);
+
+/* One iteration of Algorithm 1 for this partition: sample, induced subgraph (+ transpose), L
+ * layers forward, loss summed over inner nodes, backward, optional SGD w <- w - lr * g.
+ *   X dev f32[n_in*d_0]; halo_h host array of L dev pointers, halo_h[l] = f32[n_halo*d_l];
+ *   labels dev (see loss_kind); W host array of L dev pointers f32[d_{l}*d_{l+1}], updated in
+ *   place iff lr > 0; dW host array of L dev pointers (out); dhalo NULL, or host array of L dev
+ *   pointers f32[n_halo*d_l] (entry 0 unused, NULL entries skipped); loss dev f32[1] (out).
+ * Intermediate results stay in the workspace and can be located with bns_ws_view. */
+bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p, const float *X,
+                          const float *const *halo_h, const void *labels, float *const *W,
+                          float *const *dW, float *const *dhalo, float *loss, float lr,
+                          void *stream);
+
+/* Where bns_train_step keeps its intermediates inside the workspace (for inspection). */
+typedef enum {
+  BNS_VIEW_KEPT_IDS = 0,  /* int32[n_halo]            */
+  BNS_VIEW_REMAP = 1,     /* int32[n_halo]            */
+  BNS_VIEW_N_KEPT = 2,    /* int32[1]                 */
+  BNS_VIEW_ROW_PTR = 3,   /* int32[n_in+1]            */
+  BNS_VIEW_COL_IDX = 4,   /* int32[nnz0]              */
+  BNS_VIEW_T_ROW_PTR = 5, /* int32[n_in+n_halo+1]     */
+  BNS_VIEW_T_COL_IDX = 6, /* int32[nnz0]              */
+  BNS_VIEW_NNZ = 7,       /* int32[1]                 */
+  BNS_VIEW_A = 8,         /* layer l: f32[n_in*d_{l-1}], l = 1..L */
+  BNS_VIEW_H = 9          /* layer l: f32[n_in*d_l],     l = 1..L (H_L = logits) */
+} bns_view;
+bns_status bns_ws_view(const bns_ctx *ctx, bns_view which, int32_t layer, void **dev_ptr,
+                       size_t *bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BNS_GCN_H */

@@ -155,9 +155,10 @@ def halo_scale(p: float, n_kept: int) -> float:
     return 1.0 / p if n_kept > 0 else 1.0
 
 
-def forward(part, sub, X, halo_h, W, p):
+def forward(part, sub, X, halo_h, W, p, Z_out=None):
     """All layers.  ``sub`` = dict(row_ptr, col_idx, kept_ids).  -> (A list, H list) with
-    H[0] = X, H[l] = ReLU(A[l] W[l]) for l < L and H[L] = A[L] W[L] (logits)."""
+    H[0] = X, H[l] = ReLU(A[l] W[l]) for l < L and H[L] = A[L] W[L] (logits).  If ``Z_out`` is a
+    list, the pre-activations A[l] W[l] are appended to it (index l-1)."""
     L = len(W)
     s = halo_scale(p, sub["kept_ids"].shape[0])
     H = [np.asarray(X, dtype=np.float64)]
@@ -167,6 +168,8 @@ def forward(part, sub, X, halo_h, W, p):
         z = a @ np.asarray(W[l - 1], dtype=np.float64)
         A.append(a)
         H.append(np.maximum(z, 0.0) if l < L else z)
+        if Z_out is not None:
+            Z_out.append(z)
     return A, H
 
 
@@ -224,10 +227,11 @@ def sample_and_build(part, seed, epoch, p):
 def step(part, loss_kind, X, halo_h, labels, W, seed, epoch, p, lr=0.0):
     """One iteration of Algorithm 1 on one partition (no exchange, optional SGD)."""
     sub = sample_and_build(part, seed, epoch, p)
-    A, H = forward(part, sub, X, halo_h, W, p)
+    Z = []
+    A, H = forward(part, sub, X, halo_h, W, p, Z_out=Z)
     loss, dZ = loss_and_grad(H[-1], labels, loss_kind)
     dW, dhalo, dH = backward(part, sub, A, H, W, dZ, p)
-    out = dict(sub=sub, A=A, H=H, loss=loss, dZ_last=dZ, dW=dW, dhalo=dhalo, dH=dH)
+    out = dict(sub=sub, A=A, H=H, Z=[None] + Z, loss=loss, dZ_last=dZ, dW=dW, dhalo=dhalo, dH=dH)
     if lr > 0.0:
         out["W_new"] = [np.asarray(w, dtype=np.float64) - lr * g for w, g in zip(W, dW)]
     return out

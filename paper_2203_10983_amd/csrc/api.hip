@@ -1,0 +1,368 @@
+// C ABI of the BNS-GCN partition step: context, workspace carving, argument checks and the
+// sequencing of the kernels.  See include/bns_gcn.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/bns_gcn.h"
+#include "kernels.hpp"
+
+using namespace bns;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Walks the workspace once; used both to size it and to hand out pointers.
+struct Carver {
+  char *base;
+  size_t off = 0;
+  explicit Carver(void *b) : base(static_cast<char *>(b)) {}
+  template <typename T> T *take(size_t count) {
+    T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+    off += align_up(count * sizeof(T));
+    return p;
+  }
+};
+
+struct Layout {
+  // static, filled at set-up
+  float *dis_in, *dis_halo;
+  StaticSplit split;
+  // scratch shared by all calls
+  int32_t *tile_sums;
+  uint64_t *ballots;
+  int32_t *kpos, *hlen;
+  float *Hu, *G0, *G1, *partials, *loss_partials;
+  // state of bns_train_step
+  int32_t *kept_ids, *remap, *counters;
+  int32_t *row_ptr, *col_idx, *t_row_ptr, *t_col_idx;
+  std::vector<float *> A, H;  // index 1..L
+};
+
+}  // namespace
+
+struct bns_ctx {
+  bns_partition_desc part;
+  std::vector<int32_t> dims;
+  int32_t n_layers, loss_kind;
+  Layout ws;
+  // latest sample / subgraph the layer calls work on
+  const int32_t *cur_kept = nullptr, *cur_remap = nullptr, *cur_n_kept = nullptr;
+  const int32_t *cur_row_ptr = nullptr, *cur_col_idx = nullptr, *cur_t_row_ptr = nullptr,
+                *cur_t_col_idx = nullptr;
+  std::string err;
+};
+
+namespace {
+
+bool valid_desc(const bns_partition_desc *p, const bns_model_desc *m) {
+  if (!p || !m || !m->dims) return false;
+  if (p->n_in < 1 || p->n_halo < 0 || p->nnz0 < p->n_in || p->e_in < p->n_in || p->e_bd < 0) return false;
+  if (p->e_in + p->e_bd != p->nnz0) return false;
+  if (m->n_layers < 1 || (m->loss_kind != 0 && m->loss_kind != 1)) return false;
+  for (int l = 0; l <= m->n_layers; ++l)
+    if (m->dims[l] < 1 || m->dims[l] > 2048) return false;
+  return true;
+}
+
+bool fits_int32(const bns_partition_desc *p, const bns_model_desc *m) {
+  const int64_t lim = INT32_MAX;
+  if (p->nnz0 >= lim || (int64_t)p->n_in + p->n_halo + 1 >= lim) return false;
+  int64_t dmax = 0;
+  for (int l = 0; l <= m->n_layers; ++l) dmax = std::max<int64_t>(dmax, m->dims[l]);
+  return ((int64_t)p->n_in + p->n_halo) * dmax < (int64_t)1 << 40;  // byte offsets are 64-bit
+}
+
+size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, Layout *out) {
+  const size_t n_in = p->n_in, B = p->n_halo, L = m->n_layers;
+  size_t d_in_max = 0, d_max = 0, part_max = 0;
+  for (size_t l = 0; l <= L; ++l) d_max = std::max<size_t>(d_max, m->dims[l]);
+  for (size_t l = 0; l < L; ++l) {
+    d_in_max = std::max<size_t>(d_in_max, m->dims[l]);
+    const size_t mn = (size_t)m->dims[l] * m->dims[l + 1];
+    part_max = std::max(part_max, mn * (size_t)splitk_splits(m->dims[l], m->dims[l + 1], p->n_in));
+  }
+  Layout w;
+  w.dis_in = c.take<float>(n_in);
+  w.dis_halo = c.take<float>(B);
+  w.split.n_inner = c.take<int32_t>(n_in);
+  w.split.inner_ptr = c.take<int32_t>(n_in + 1);
+  w.split.bd_ptr = c.take<int32_t>(n_in + 1);
+  w.split.in_col = c.take<int32_t>(p->e_in);
+  w.split.in_row = c.take<int32_t>(p->e_in);
+  w.split.bd_b = c.take<int32_t>(p->e_bd);
+  w.split.bd_row = c.take<int32_t>(p->e_bd);
+  w.tile_sums = c.take<int32_t>(scan_tiles(p->nnz0 + n_in + B) + 4);
+  w.ballots = c.take<uint64_t>((B + 63) / 64 + 1);
+  w.kpos = c.take<int32_t>(p->e_bd + 1);
+  w.hlen = c.take<int32_t>(B + 1);
+  w.Hu = c.take<float>(B * d_in_max);
+  w.G0 = c.take<float>(n_in * d_max);
+  w.G1 = c.take<float>(n_in * d_max);
+  w.partials = c.take<float>(part_max);
+  w.loss_partials = c.take<float>(kLossBlocks);
+  w.kept_ids = c.take<int32_t>(B + 1);
+  w.remap = c.take<int32_t>(B + 1);
+  w.counters = c.take<int32_t>(64);
+  w.row_ptr = c.take<int32_t>(n_in + 1);
+  w.col_idx = c.take<int32_t>(p->nnz0);
+  w.t_row_ptr = c.take<int32_t>(n_in + B + 1);
+  w.t_col_idx = c.take<int32_t>(p->nnz0);
+  w.A.assign(L + 1, nullptr);
+  w.H.assign(L + 1, nullptr);
+  for (size_t l = 1; l <= L; ++l) {
+    w.A[l] = c.take<float>(n_in * (size_t)m->dims[l - 1]);
+    w.H[l] = c.take<float>(n_in * (size_t)m->dims[l]);
+  }
+  if (out) *out = w;
+  return c.off;
+}
+
+bns_status fail(bns_ctx *ctx, bns_status st, const std::string &msg) {
+  if (ctx) ctx->err = msg;
+  return st;
+}
+
+bns_status hip_fail(bns_ctx *ctx, const char *what, hipError_t e) {
+  return fail(ctx, BNS_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define BNS_TRY(what, expr)                                   \
+  do {                                                        \
+    hipError_t _e = (expr);                                   \
+    if (_e != hipSuccess) return hip_fail(ctx, what, _e);     \
+  } while (0)
+
+bool bad_p(double p) { return !(p >= 0.0 && p <= 1.0); }
+float halo_scale(double p) { return p > 0.0 ? (float)(1.0 / p) : 0.f; }  // 1/p is never formed at p = 0
+
+bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, const float *halo_h,
+                          const float *W, float *A_saved, float *H_out, bool relu, hipStream_t s) {
+  const int n_in = ctx->part.n_in, B = ctx->part.n_halo;
+  const int d_in = ctx->dims[layer - 1], d_out = ctx->dims[layer];
+  BNS_TRY("halo_gather", halo_gather(halo_h, ctx->cur_kept, ctx->cur_n_kept, B, ctx->ws.dis_halo,
+                                     halo_scale(p), d_in, ctx->ws.Hu, s));
+  BNS_TRY("spmm_fwd", spmm_fwd(n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx, ctx->ws.dis_in, H_in,
+                               ctx->ws.Hu, A_saved, s));
+  BNS_TRY("gemm_nn", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, relu, s));
+  return BNS_OK;
+}
+
+// dZ is the gradient of the layer's pre-activation.  mask_src (nullable): activations of the
+// layer below; when given, dH_in receives the masked gradient (= dZ of the layer below).
+bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, const float *A_saved,
+                          const float *W, float *dW, float *dH_in, float *dhalo,
+                          const float *mask_src, hipStream_t s) {
+  const int n_in = ctx->part.n_in, B = ctx->part.n_halo;
+  const int d_in = ctx->dims[layer - 1], d_out = ctx->dims[layer];
+  BNS_TRY("gemm_tn_splitk", gemm_tn_splitk(d_in, d_out, n_in, A_saved, dZ, dW, ctx->ws.partials, s));
+  if (dH_in) {
+    BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, s));
+    BNS_TRY("spmm_bwd", spmm_bwd(n_in, B, d_in, ctx->cur_t_row_ptr, ctx->cur_t_col_idx, ctx->cur_kept,
+                                 ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_halo, halo_scale(p),
+                                 ctx->ws.G1, mask_src, dH_in, dhalo, s));
+  }
+  return BNS_OK;
+}
+
+bns_status sample_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p, int32_t *kept_ids,
+                       int32_t *remap, int32_t *n_kept, hipStream_t s) {
+  const uint64_t threshold = (uint64_t)std::floor(p * 4294967296.0);
+  BNS_TRY("sample_boundary",
+          sample_boundary(ctx->part.halo_gid, ctx->part.n_halo, seed, epoch, (uint32_t)ctx->part.part_id,
+                          threshold, ctx->ws.ballots, ctx->ws.tile_sums, kept_ids, remap, n_kept, s));
+  ctx->cur_kept = kept_ids;
+  ctx->cur_remap = remap;
+  ctx->cur_n_kept = n_kept;
+  return BNS_OK;
+}
+
+bns_status build_impl(bns_ctx *ctx, int32_t *row_ptr, int32_t *col_idx, int32_t *t_row_ptr,
+                      int32_t *t_col_idx, int32_t *nnz, hipStream_t s) {
+  const bns_partition_desc &P = ctx->part;
+  BNS_TRY("build_sampled_csr",
+          build_sampled_csr(P.n_in, P.e_in, P.e_bd, ctx->ws.split, ctx->cur_remap, ctx->ws.kpos,
+                            ctx->ws.tile_sums, row_ptr, col_idx, nnz, s));
+  BNS_TRY("build_transposed_csr",
+          build_transposed_csr(P.n_in, P.n_halo, P.e_in, P.t_in_ptr, P.t_in_col, P.halo_ptr, P.halo_col,
+                               ctx->cur_kept, ctx->cur_n_kept, ctx->ws.hlen, ctx->ws.tile_sums,
+                               t_row_ptr, t_col_idx, s));
+  ctx->cur_row_ptr = row_ptr;
+  ctx->cur_col_idx = col_idx;
+  ctx->cur_t_row_ptr = t_row_ptr;
+  ctx->cur_t_col_idx = t_col_idx;
+  return BNS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t bns_workspace_bytes(const bns_partition_desc *part, const bns_model_desc *model) {
+  if (!valid_desc(part, model) || !fits_int32(part, model)) return 0;
+  Carver c(nullptr);
+  return carve(c, part, model, nullptr);
+}
+
+bns_status bns_create(bns_ctx **out, const bns_partition_desc *part, const bns_model_desc *model,
+                      void *dev_ws, size_t ws_bytes, void *stream) {
+  if (!out) return BNS_EINVAL;
+  *out = nullptr;
+  if (!valid_desc(part, model)) return BNS_EINVAL;
+  if (!fits_int32(part, model)) return BNS_EOVERFLOW;
+  if (!part->row_ptr0 || !part->col0 || !part->t_in_ptr || !part->t_in_col || !part->deg_in) return BNS_EINVAL;
+  if (part->n_halo > 0 && (!part->halo_ptr || !part->halo_col || !part->halo_gid || !part->deg_halo))
+    return BNS_EINVAL;
+  if (!dev_ws || ((uintptr_t)dev_ws % kAlign) != 0) return BNS_EWORKSPACE;
+  bns_ctx *ctx = new (std::nothrow) bns_ctx();
+  if (!ctx) return BNS_EINVAL;
+  ctx->part = *part;
+  ctx->n_layers = model->n_layers;
+  ctx->loss_kind = model->loss_kind;
+  ctx->dims.assign(model->dims, model->dims + model->n_layers + 1);
+  Carver c(dev_ws);
+  const size_t need = carve(c, part, model, &ctx->ws);
+  if (need > ws_bytes) { delete ctx; return BNS_EWORKSPACE; }
+  *out = ctx;  // handed out even if set-up fails, so that the caller can read the error text
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  BNS_TRY("degree_rsqrt(in)", degree_rsqrt(part->deg_in, part->n_in, ctx->ws.dis_in, s));
+  BNS_TRY("degree_rsqrt(halo)", degree_rsqrt(part->deg_halo, part->n_halo, ctx->ws.dis_halo, s));
+  BNS_TRY("build_static_split", build_static_split(part->n_in, part->row_ptr0, part->col0, ctx->ws.split,
+                                                   ctx->ws.tile_sums, s));
+  BNS_TRY("set-up sync", hipStreamSynchronize(s));
+  return BNS_OK;
+}
+
+void bns_destroy(bns_ctx *ctx) { delete ctx; }
+
+const char *bns_last_error(const bns_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+bns_status bns_sample_boundary(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p, int32_t *kept_ids,
+                               int32_t *remap, int32_t *n_kept, void *stream) {
+  if (!ctx) return BNS_EINVAL;
+  if (bad_p(p)) return fail(ctx, BNS_EINVAL, "p must lie in [0, 1]");
+  if (!n_kept || (ctx->part.n_halo > 0 && (!kept_ids || !remap)))
+    return fail(ctx, BNS_EINVAL, "null output pointer");
+  return sample_impl(ctx, seed, epoch, p, kept_ids, remap, n_kept, static_cast<hipStream_t>(stream));
+}
+
+bns_status bns_build_sampled_csr(bns_ctx *ctx, int32_t *row_ptr, int32_t *col_idx, int32_t *t_row_ptr,
+                                 int32_t *t_col_idx, int32_t *nnz, void *stream) {
+  if (!ctx) return BNS_EINVAL;
+  if (!row_ptr || !col_idx || !t_row_ptr || !t_col_idx || !nnz)
+    return fail(ctx, BNS_EINVAL, "null output pointer");
+  if (!ctx->cur_n_kept) return fail(ctx, BNS_EINVAL, "bns_sample_boundary has not been called");
+  return build_impl(ctx, row_ptr, col_idx, t_row_ptr, t_col_idx, nnz, static_cast<hipStream_t>(stream));
+}
+
+bns_status bns_gcn_layer_fwd(bns_ctx *ctx, int32_t layer, double p, const float *H_in, const float *halo_h,
+                             const float *W, float *A_saved, float *H_out, int32_t relu, void *stream) {
+  if (!ctx) return BNS_EINVAL;
+  if (layer < 1 || layer > ctx->n_layers) return fail(ctx, BNS_EINVAL, "layer out of range");
+  if (bad_p(p)) return fail(ctx, BNS_EINVAL, "p must lie in [0, 1]");
+  if (!H_in || !W || !A_saved || !H_out || (ctx->part.n_halo > 0 && !halo_h))
+    return fail(ctx, BNS_EINVAL, "null pointer");
+  if (!ctx->cur_row_ptr) return fail(ctx, BNS_EINVAL, "bns_build_sampled_csr has not been called");
+  return layer_fwd_impl(ctx, layer, p, H_in, halo_h, W, A_saved, H_out, relu != 0,
+                        static_cast<hipStream_t>(stream));
+}
+
+bns_status bns_gcn_layer_bwd(bns_ctx *ctx, int32_t layer, double p, const float *dH_out, const float *H_out,
+                             const float *A_saved, const float *W, float *dW, float *dH_in, float *dhalo,
+                             void *stream) {
+  if (!ctx) return BNS_EINVAL;
+  if (layer < 1 || layer > ctx->n_layers) return fail(ctx, BNS_EINVAL, "layer out of range");
+  if (bad_p(p)) return fail(ctx, BNS_EINVAL, "p must lie in [0, 1]");
+  if (!dH_out || !A_saved || !W || !dW) return fail(ctx, BNS_EINVAL, "null pointer");
+  if (!dH_in && dhalo) return fail(ctx, BNS_EINVAL, "dhalo needs dH_in");
+  if (!ctx->cur_t_row_ptr) return fail(ctx, BNS_EINVAL, "bns_build_sampled_csr has not been called");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const float *dZ = dH_out;
+  if (H_out) {
+    const int64_t n = (int64_t)ctx->part.n_in * ctx->dims[layer];
+    BNS_TRY("relu_mask", relu_mask(n, dH_out, H_out, ctx->ws.G0, s));
+    dZ = ctx->ws.G0;
+  }
+  return layer_bwd_impl(ctx, layer, p, dZ, A_saved, W, dW, dH_in, dhalo, nullptr, s);
+}
+
+bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p, const float *X,
+                          const float *const *halo_h, const void *labels, float *const *W, float *const *dW,
+                          float *const *dhalo, float *loss, float lr, void *stream) {
+  if (!ctx) return BNS_EINVAL;
+  if (bad_p(p)) return fail(ctx, BNS_EINVAL, "p must lie in [0, 1]");
+  if (!X || !labels || !W || !dW || !loss || (ctx->part.n_halo > 0 && !halo_h))
+    return fail(ctx, BNS_EINVAL, "null pointer");
+  const int L = ctx->n_layers, n_in = ctx->part.n_in;
+  for (int l = 0; l < L; ++l)
+    if (!W[l] || !dW[l] || (ctx->part.n_halo > 0 && !halo_h[l])) return fail(ctx, BNS_EINVAL, "null layer pointer");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Layout &w = ctx->ws;
+
+  bns_status st = sample_impl(ctx, seed, epoch, p, w.kept_ids, w.remap, w.counters, s);
+  if (st != BNS_OK) return st;
+  st = build_impl(ctx, w.row_ptr, w.col_idx, w.t_row_ptr, w.t_col_idx, w.counters + 1, s);
+  if (st != BNS_OK) return st;
+
+  const float *H_prev = X;
+  for (int l = 1; l <= L; ++l) {
+    st = layer_fwd_impl(ctx, l, p, H_prev, ctx->part.n_halo > 0 ? halo_h[l - 1] : nullptr, W[l - 1], w.A[l],
+                        w.H[l], l < L, s);
+    if (st != BNS_OK) return st;
+    H_prev = w.H[l];
+  }
+
+  const int C = ctx->dims[L];
+  if (ctx->loss_kind == 0)
+    BNS_TRY("loss_softmax_ce", loss_softmax_ce(n_in, C, w.H[L], static_cast<const int32_t *>(labels), w.G0,
+                                               w.loss_partials, loss, s));
+  else
+    BNS_TRY("loss_sigmoid_bce", loss_sigmoid_bce(n_in, C, w.H[L], static_cast<const uint8_t *>(labels), w.G0,
+                                                 w.loss_partials, loss, s));
+
+  // G0 holds dZ of the current layer; the transposed aggregate writes the next dZ back into it,
+  // masked by the activations of the layer below
+  for (int l = L; l >= 1; --l) {
+    float *dh = (dhalo && l > 1) ? dhalo[l - 1] : nullptr;
+    st = layer_bwd_impl(ctx, l, p, w.G0, w.A[l], W[l - 1], dW[l - 1], l > 1 ? w.G0 : nullptr, dh,
+                        l > 1 ? w.H[l - 1] : nullptr, s);
+    if (st != BNS_OK) return st;
+  }
+  if (lr > 0.f)
+    for (int l = 0; l < L; ++l)
+      BNS_TRY("sgd_update", sgd_update((int64_t)ctx->dims[l] * ctx->dims[l + 1], W[l], dW[l], lr, s));
+  return BNS_OK;
+}
+
+bns_status bns_ws_view(const bns_ctx *ctx, bns_view which, int32_t layer, void **dev_ptr, size_t *bytes) {
+  if (!ctx || !dev_ptr || !bytes) return BNS_EINVAL;
+  const Layout &w = ctx->ws;
+  const size_t n_in = ctx->part.n_in, B = ctx->part.n_halo, nnz0 = ctx->part.nnz0;
+  switch (which) {
+    case BNS_VIEW_KEPT_IDS: *dev_ptr = w.kept_ids; *bytes = 4 * B; break;
+    case BNS_VIEW_REMAP: *dev_ptr = w.remap; *bytes = 4 * B; break;
+    case BNS_VIEW_N_KEPT: *dev_ptr = w.counters; *bytes = 4; break;
+    case BNS_VIEW_ROW_PTR: *dev_ptr = w.row_ptr; *bytes = 4 * (n_in + 1); break;
+    case BNS_VIEW_COL_IDX: *dev_ptr = w.col_idx; *bytes = 4 * nnz0; break;
+    case BNS_VIEW_T_ROW_PTR: *dev_ptr = w.t_row_ptr; *bytes = 4 * (n_in + B + 1); break;
+    case BNS_VIEW_T_COL_IDX: *dev_ptr = w.t_col_idx; *bytes = 4 * nnz0; break;
+    case BNS_VIEW_NNZ: *dev_ptr = w.counters + 1; *bytes = 4; break;
+    case BNS_VIEW_A:
+    case BNS_VIEW_H:
+      if (layer < 1 || layer > ctx->n_layers) return BNS_EINVAL;
+      if (which == BNS_VIEW_A) { *dev_ptr = w.A[layer]; *bytes = 4 * n_in * (size_t)ctx->dims[layer - 1]; }
+      else { *dev_ptr = w.H[layer]; *bytes = 4 * n_in * (size_t)ctx->dims[layer]; }
+      break;
+    default: return BNS_EINVAL;
+  }
+  return BNS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,220 @@
+// Node-induced subgraph on the inner nodes plus the kept boundary nodes (Algorithm 1, subgraph
+// step), as a canonical CSR, and its transpose for the backward pass.
+//
+// Columns are ascending in a row, so the boundary entries are each row's tail.  Once, at set-up,
+// the static CSR is split into its inner entries and its boundary entries (both row-major, each
+// with its row).  Per epoch only the boundary entries are filtered (the work is proportional to
+// the number of boundary edges, Appendix D): an entry-parallel prefix sum over their keep flags
+// gives every kept boundary entry, every inner entry and every row start its final position
+// without any per-row loop, so power-law rows cost nothing extra.
+//
+//   kpos[k]     = kept boundary entries before boundary entry k            (prefix sum)
+//   row_ptr[v]  = inner_ptr[v] + kpos[bd_ptr[v]]
+//   inner entry j of row v      -> col_idx[j + row_ptr[v] - inner_ptr[v]]
+//   kept boundary entry k, row v -> col_idx[inner_ptr[v+1] + kpos[k]]
+#include "device_utils.hpp"
+#include "kernels.hpp"
+
+namespace bns {
+
+constexpr int kThreads = 256;
+constexpr int kItems = kScanTile / kThreads;
+
+// ---------------------------------------------------------------------------------- set-up
+__global__ void __launch_bounds__(kThreads)
+count_inner_kernel(int32_t n_in, const int32_t *__restrict__ row_ptr0,
+                   const int32_t *__restrict__ col0, int32_t *__restrict__ n_inner) {
+  const int v = blockIdx.x * kThreads + threadIdx.x;
+  if (v >= n_in) return;
+  int lo = row_ptr0[v], hi = row_ptr0[v + 1];
+  const int start = lo;
+  while (lo < hi) {  // first entry whose column is a boundary column
+    const int mid = (lo + hi) >> 1;
+    if (col0[mid] < n_in) lo = mid + 1; else hi = mid;
+  }
+  n_inner[v] = lo - start;
+}
+
+// One wavefront per row scatters the row's entries into the inner and boundary lists.
+__global__ void __launch_bounds__(kThreads)
+split_entries_kernel(int32_t n_in, const int32_t *__restrict__ row_ptr0,
+                     const int32_t *__restrict__ col0, const int32_t *__restrict__ inner_ptr,
+                     int32_t *__restrict__ bd_ptr, int32_t *__restrict__ in_col,
+                     int32_t *__restrict__ in_row, int32_t *__restrict__ bd_b,
+                     int32_t *__restrict__ bd_row) {
+  const int lane = lane_id();
+  const int waves = gridDim.x * (kThreads / kWave);
+  for (int v = blockIdx.x * (kThreads / kWave) + threadIdx.x / kWave; v <= n_in; v += waves) {
+    if (v == n_in) {
+      if (lane == 0) bd_ptr[n_in] = row_ptr0[n_in] - inner_ptr[n_in];
+      continue;
+    }
+    const int e0 = row_ptr0[v], e1 = row_ptr0[v + 1];
+    const int i0 = inner_ptr[v], ni = inner_ptr[v + 1] - i0;
+    const int b0 = e0 - i0;
+    if (lane == 0) bd_ptr[v] = b0;
+    for (int e = e0 + lane; e < e1; e += kWave) {
+      const int c = col0[e];
+      const int o = e - e0;
+      if (o < ni) { in_col[i0 + o] = c; in_row[i0 + o] = v; }
+      else { bd_b[b0 + o - ni] = c - n_in; bd_row[b0 + o - ni] = v; }
+    }
+  }
+}
+
+__global__ void __launch_bounds__(kThreads)
+degree_rsqrt_kernel(const int32_t *__restrict__ deg, int32_t n, float *__restrict__ dis) {
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  if (i < n) dis[i] = 1.0f / sqrtf((float)deg[i]);
+}
+
+hipError_t degree_rsqrt(const int32_t *deg, int32_t n, float *dis, hipStream_t s) {
+  if (n > 0) degree_rsqrt_kernel<<<(n + kThreads - 1) / kThreads, kThreads, 0, s>>>(deg, n, dis);
+  return hipGetLastError();
+}
+
+hipError_t build_static_split(int32_t n_in, const int32_t *row_ptr0, const int32_t *col0,
+                              const StaticSplit &sp, int32_t *tile_sums, hipStream_t s) {
+  count_inner_kernel<<<(n_in + kThreads - 1) / kThreads, kThreads, 0, s>>>(n_in, row_ptr0, col0,
+                                                                           sp.n_inner);
+  hipError_t e = scan_exclusive_i32(sp.n_inner, sp.inner_ptr, n_in, nullptr, tile_sums, nullptr, 0, s);
+  if (e != hipSuccess) return e;
+  const int blocks = (n_in + 1 + (kThreads / kWave) - 1) / (kThreads / kWave);
+  split_entries_kernel<<<blocks < 65536 ? blocks : 65536, kThreads, 0, s>>>(
+      n_in, row_ptr0, col0, sp.inner_ptr, sp.bd_ptr, sp.in_col, sp.in_row, sp.bd_b, sp.bd_row);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------- per epoch
+__global__ void __launch_bounds__(kThreads)
+bd_keep_tile_sums_kernel(int64_t e_bd, const int32_t *__restrict__ bd_b,
+                         const int32_t *__restrict__ remap, int32_t *__restrict__ tile_sums) {
+  const int64_t k0 = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kItems;
+  int cnt = 0;
+#pragma unroll
+  for (int i = 0; i < kItems; ++i)
+    if (k0 + i < e_bd) cnt += remap[bd_b[k0 + i]] >= 0;
+  int total;
+  block_exclusive_scan<kThreads>(cnt, &total);
+  if (threadIdx.x == 0) tile_sums[blockIdx.x] = total;
+}
+
+__global__ void __launch_bounds__(kThreads)
+bd_fill_kernel(int32_t n_in, int64_t e_bd, const int32_t *__restrict__ bd_b,
+               const int32_t *__restrict__ bd_row, const int32_t *__restrict__ remap,
+               const int32_t *__restrict__ tile_offsets, const int32_t *__restrict__ inner_ptr,
+               int32_t *__restrict__ kpos, int32_t *__restrict__ col_idx) {
+  const int64_t k0 = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kItems;
+  int rank[kItems];
+  int cnt = 0;
+#pragma unroll
+  for (int i = 0; i < kItems; ++i) {
+    rank[i] = (k0 + i < e_bd) ? remap[bd_b[k0 + i]] : -1;
+    cnt += rank[i] >= 0;
+  }
+  int total;
+  int run = tile_offsets[blockIdx.x] + block_exclusive_scan<kThreads>(cnt, &total);
+#pragma unroll
+  for (int i = 0; i < kItems; ++i) {
+    const int64_t k = k0 + i;
+    if (k < e_bd) {
+      kpos[k] = run;
+      if (rank[i] >= 0) {
+        col_idx[inner_ptr[bd_row[k] + 1] + run] = n_in + rank[i];
+        ++run;
+      }
+      if (k == e_bd - 1) kpos[e_bd] = run;
+    }
+  }
+}
+
+__global__ void __launch_bounds__(kThreads)
+row_ptr_kernel(int32_t n_in, int64_t e_bd, const int32_t *__restrict__ inner_ptr,
+               const int32_t *__restrict__ bd_ptr, const int32_t *__restrict__ kpos,
+               int32_t *__restrict__ row_ptr, int32_t *__restrict__ nnz) {
+  const int v = blockIdx.x * kThreads + threadIdx.x;
+  if (v > n_in) return;
+  const int r = inner_ptr[v] + (e_bd > 0 ? kpos[bd_ptr[v]] : 0);
+  row_ptr[v] = r;
+  if (v == n_in) *nnz = r;
+}
+
+__global__ void __launch_bounds__(kThreads)
+inner_fill_kernel(int64_t e_in, const int32_t *__restrict__ in_col,
+                  const int32_t *__restrict__ in_row, const int32_t *__restrict__ row_ptr,
+                  const int32_t *__restrict__ inner_ptr, int32_t *__restrict__ col_idx) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < e_in; j += stride) {
+    const int v = in_row[j];
+    col_idx[j + (row_ptr[v] - inner_ptr[v])] = in_col[j];
+  }
+}
+
+hipError_t build_sampled_csr(int32_t n_in, int64_t e_in, int64_t e_bd, const StaticSplit &sp,
+                             const int32_t *remap, int32_t *kpos, int32_t *tile_sums,
+                             int32_t *row_ptr, int32_t *col_idx, int32_t *nnz, hipStream_t s) {
+  if (e_bd > 0) {
+    const int nb = scan_tiles(e_bd);
+    bd_keep_tile_sums_kernel<<<nb, kThreads, 0, s>>>(e_bd, sp.bd_b, remap, tile_sums);
+    (void)scan_sums_inplace(tile_sums, nb, nullptr, s);
+    bd_fill_kernel<<<nb, kThreads, 0, s>>>(n_in, e_bd, sp.bd_b, sp.bd_row, remap, tile_sums,
+                                           sp.inner_ptr, kpos, col_idx);
+  }
+  row_ptr_kernel<<<(n_in + 1 + kThreads - 1) / kThreads, kThreads, 0, s>>>(
+      n_in, e_bd, sp.inner_ptr, sp.bd_ptr, kpos, row_ptr, nnz);
+  int64_t blocks = (e_in + kThreads * 4 - 1) / (kThreads * 4);
+  if (blocks < 1) blocks = 1;
+  inner_fill_kernel<<<(unsigned)blocks, kThreads, 0, s>>>(e_in, sp.in_col, sp.in_row, row_ptr,
+                                                          sp.inner_ptr, col_idx);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------- transpose
+__global__ void __launch_bounds__(kThreads)
+kept_len_kernel(const int32_t *__restrict__ n_kept, const int32_t *__restrict__ kept_ids,
+                const int32_t *__restrict__ halo_ptr, int32_t *__restrict__ hlen) {
+  const int r = blockIdx.x * kThreads + threadIdx.x;
+  if (r >= *n_kept) return;
+  const int b = kept_ids[r];
+  hlen[r] = halo_ptr[b + 1] - halo_ptr[b];
+}
+
+// Eight lanes copy one kept boundary node's list of inner rows.
+__global__ void __launch_bounds__(kThreads)
+kept_rows_fill_kernel(const int32_t *__restrict__ n_kept, const int32_t *__restrict__ kept_ids,
+                      const int32_t *__restrict__ halo_ptr, const int32_t *__restrict__ halo_col,
+                      const int32_t *__restrict__ t_tail_ptr, int32_t *__restrict__ t_col_idx) {
+  const int r = (blockIdx.x * kThreads + threadIdx.x) >> 3;
+  const int sub = threadIdx.x & 7;
+  if (r >= *n_kept) return;
+  const int b = kept_ids[r];
+  const int src = halo_ptr[b], len = halo_ptr[b + 1] - src;
+  const int dst = t_tail_ptr[r];
+  for (int i = sub; i < len; i += 8) t_col_idx[dst + i] = halo_col[src + i];
+}
+
+hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
+                                const int32_t *t_in_ptr, const int32_t *t_in_col,
+                                const int32_t *halo_ptr, const int32_t *halo_col,
+                                const int32_t *kept_ids, const int32_t *n_kept, int32_t *hlen,
+                                int32_t *tile_sums, int32_t *t_row_ptr, int32_t *t_col_idx,
+                                hipStream_t s) {
+  // rows of inner nodes never change: the transpose of the inner-inner block
+  hipError_t e = hipMemcpyAsync(t_row_ptr, t_in_ptr, sizeof(int32_t) * ((size_t)n_in + 1),
+                                hipMemcpyDeviceToDevice, s);
+  if (e != hipSuccess) return e;
+  e = hipMemcpyAsync(t_col_idx, t_in_col, sizeof(int32_t) * (size_t)e_in, hipMemcpyDeviceToDevice, s);
+  if (e != hipSuccess) return e;
+  if (n_halo == 0) return hipSuccess;
+  // rows of kept boundary nodes: their static lists of inner neighbours, in kept order
+  kept_len_kernel<<<(n_halo + kThreads - 1) / kThreads, kThreads, 0, s>>>(n_kept, kept_ids,
+                                                                         halo_ptr, hlen);
+  e = scan_exclusive_i32(hlen, t_row_ptr + n_in, n_halo, n_kept, tile_sums, nullptr, (int32_t)e_in, s);
+  if (e != hipSuccess) return e;
+  const int64_t threads = (int64_t)n_halo * 8;
+  kept_rows_fill_kernel<<<(unsigned)((threads + kThreads - 1) / kThreads), kThreads, 0, s>>>(
+      n_kept, kept_ids, halo_ptr, halo_col, t_row_ptr + n_in, t_col_idx);
+  return hipGetLastError();
+}
+
+}  // namespace bns

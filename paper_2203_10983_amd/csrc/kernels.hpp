@@ -1,0 +1,97 @@
+// Host-side launchers of the gfx950 kernels.  Every launcher enqueues on `s` and returns the
+// launch status; none synchronises.  Pointers are device pointers unless named *_host.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bns {
+
+constexpr int kScanTile = 2048;  // elements per block in the scan / compaction kernels
+inline int scan_tiles(int64_t n) { return (int)((n + kScanTile - 1) / kScanTile); }
+
+// ---- scan.hip -------------------------------------------------------------------------------
+// out[i] = add_base + sum_{j<i} in[j] for i in 0..n (n+1 entries written).  n = *n_dev if n_dev
+// is non-null (n <= n_max), else n_max.  tile_sums: scratch int32[scan_tiles(n_max)+1].
+// total_out (nullable): receives sum of all n inputs.
+hipError_t scan_exclusive_i32(const int32_t *in, int32_t *out, int64_t n_max, const int32_t *n_dev,
+                              int32_t *tile_sums, int32_t *total_out, int32_t add_base,
+                              hipStream_t s);
+
+// sums[0..nb) -> exclusive prefixes in place; sums[nb] = *total_out (nullable) = total.
+hipError_t scan_sums_inplace(int32_t *sums, int nb, int32_t *total_out, hipStream_t s);
+
+// ---- sample.hip (Algorithm 1, selection step) -------------------------------------------------
+// ballots: scratch uint64[ceil(B/64)]; tile_sums: scratch int32[scan_tiles(B)+1].
+hipError_t sample_boundary(const int64_t *halo_gid, int32_t n_halo, uint64_t seed, uint32_t epoch,
+                           uint32_t part_id, uint64_t threshold, uint64_t *ballots,
+                           int32_t *tile_sums, int32_t *kept_ids, int32_t *remap, int32_t *n_kept,
+                           hipStream_t s);
+
+// ---- build_csr.hip (Algorithm 1, subgraph step) -----------------------------------------------
+struct StaticSplit {       // inner / boundary split of the static CSR, built once
+  int32_t *n_inner;        // int32[n_in]       inner entries in row v (scratch of set-up)
+  int32_t *inner_ptr;      // int32[n_in+1]     inner entries before row v
+  int32_t *bd_ptr;         // int32[n_in+1]     boundary entries before row v
+  int32_t *in_col;         // int32[e_in]       inner entries, row-major
+  int32_t *in_row;         // int32[e_in]       their rows
+  int32_t *bd_b;           // int32[e_bd]       boundary entries (boundary id), row-major
+  int32_t *bd_row;         // int32[e_bd]       their rows
+};
+hipError_t build_static_split(int32_t n_in, const int32_t *row_ptr0, const int32_t *col0,
+                              const StaticSplit &sp, int32_t *tile_sums, hipStream_t s);
+hipError_t degree_rsqrt(const int32_t *deg, int32_t n, float *dis, hipStream_t s);
+
+// kpos: scratch int32[e_bd+1]; tile_sums: scratch int32[scan_tiles(e_bd)+1].
+hipError_t build_sampled_csr(int32_t n_in, int64_t e_in, int64_t e_bd, const StaticSplit &sp,
+                             const int32_t *remap, int32_t *kpos, int32_t *tile_sums,
+                             int32_t *row_ptr, int32_t *col_idx, int32_t *nnz, hipStream_t s);
+// hlen: scratch int32[n_halo]; tile_sums: scratch int32[scan_tiles(n_halo)+1].
+hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
+                                const int32_t *t_in_ptr, const int32_t *t_in_col,
+                                const int32_t *halo_ptr, const int32_t *halo_col,
+                                const int32_t *kept_ids, const int32_t *n_kept, int32_t *hlen,
+                                int32_t *tile_sums, int32_t *t_row_ptr, int32_t *t_col_idx,
+                                hipStream_t s);
+
+// ---- spmm.hip (Eq. 1 in the sampled form of Appendix A, and its transpose) ---------------------
+// Hu[r,:] = (s_halo * dis_halo[b]) * halo_h[b,:], b = kept_ids[r], r < *n_kept.
+hipError_t halo_gather(const float *halo_h, const int32_t *kept_ids, const int32_t *n_kept,
+                       int32_t n_halo, const float *dis_halo, float s_halo, int32_t d, float *Hu,
+                       hipStream_t s);
+// A[v,:] = dis_in[v] * ( sum_{u<n_in in row v} dis_in[u] H_in[u,:] + sum_{kept r in row v} Hu[r,:] )
+hipError_t spmm_fwd(int32_t n_in, int32_t d, const int32_t *row_ptr, const int32_t *col_idx,
+                    const float *dis_in, const float *H_in, const float *Hu, float *A,
+                    hipStream_t s);
+// For stacked column u < n_in + *n_kept:  g = sum_{v in t_row u} dis_in[v] dA[v,:];
+//   u <  n_in: dH_in[u,:] = dis_in[u] * g   (zeroed where mask_src[u,:] <= 0 if mask_src != null)
+//   u >= n_in: dhalo[u-n_in,:] = s_halo * dis_halo[kept_ids[u-n_in]] * g   (skipped if dhalo null)
+hipError_t spmm_bwd(int32_t n_in, int32_t n_halo, int32_t d, const int32_t *t_row_ptr,
+                    const int32_t *t_col_idx, const int32_t *kept_ids, const int32_t *n_kept,
+                    const float *dis_in, const float *dis_halo, float s_halo, const float *dA,
+                    const float *mask_src, float *dH_in, float *dhalo, hipStream_t s);
+
+// ---- gemm.hip (Eq. 2 and its backward; fp32 MFMA) ----------------------------------------------
+// C[M,N] = A[M,K] B[K,N], optional ReLU.
+hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
+                   bool relu, hipStream_t s);
+// C[M,N] = A[M,K] B[N,K]^T.
+hipError_t gemm_nt(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
+                   hipStream_t s);
+// C[M,N] = A[K,M]^T B[K,N] with K split over the grid; partials: scratch f32[splits*M*N],
+// summed in a fixed order.  splitk_splits() gives the split count used for (M,N,K).
+int32_t splitk_splits(int32_t M, int32_t N, int32_t K);
+hipError_t gemm_tn_splitk(int32_t M, int32_t N, int32_t K, const float *A, const float *B,
+                          float *C, float *partials, hipStream_t s);
+
+// ---- loss.hip (Algorithm 1, loss step) ---------------------------------------------------------
+constexpr int kLossBlocks = 1024;  // partials: scratch f32[kLossBlocks]
+hipError_t loss_softmax_ce(int32_t n, int32_t C, const float *logits, const int32_t *labels,
+                           float *dZ, float *partials, float *loss, hipStream_t s);
+hipError_t loss_sigmoid_bce(int32_t n, int32_t C, const float *logits, const uint8_t *labels,
+                            float *dZ, float *partials, float *loss, hipStream_t s);
+// out = dH where H > 0 else 0
+hipError_t relu_mask(int64_t n, const float *dH, const float *H, float *out, hipStream_t s);
+// W -= lr * dW  (Algorithm 1, update step)
+hipError_t sgd_update(int64_t n, float *W, const float *dW, float lr, hipStream_t s);
+
+}  // namespace bns

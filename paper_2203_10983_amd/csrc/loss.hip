@@ -1,0 +1,127 @@
+// Loss summed over the inner nodes (Algorithm 1, loss step) with its gradient, the ReLU mask of
+// the backward pass and the SGD update (Algorithm 1, update step).  The loss is reduced in a
+// fixed order (per wavefront, per block, then one block over the block partials): two runs give
+// the same bits.
+#include "device_utils.hpp"
+#include "kernels.hpp"
+
+namespace bns {
+
+constexpr int kT = 256;
+
+__device__ __forceinline__ float block_sum_fixed(float x) {  // valid on thread 0
+  __shared__ float part[kT / kWave];
+  x = wave_sum(x);
+  if (lane_id() == 0) part[threadIdx.x / kWave] = x;
+  __syncthreads();
+  float s = 0.f;
+  if (threadIdx.x == 0)
+#pragma unroll
+    for (int w = 0; w < kT / kWave; ++w) s += part[w];
+  __syncthreads();
+  return s;
+}
+
+__global__ void __launch_bounds__(1024)
+final_sum_kernel(const float *__restrict__ partials, int n, float *__restrict__ out) {
+  __shared__ float part[1024 / kWave];
+  float x = 0.f;
+  for (int i = threadIdx.x; i < n; i += 1024) x += partials[i];
+  x = wave_sum(x);
+  if (lane_id() == 0) part[threadIdx.x / kWave] = x;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float s = 0.f;
+    for (int w = 0; w < 1024 / kWave; ++w) s += part[w];
+    *out = s;
+  }
+}
+
+// softmax cross-entropy: one wavefront per node; loss_v = logsumexp(z_v) - z_v[y_v],
+// dZ_v = softmax(z_v) - onehot(y_v)
+__global__ void __launch_bounds__(kT)
+softmax_ce_kernel(int n, int C, const float *__restrict__ logits, const int32_t *__restrict__ labels,
+                  float *__restrict__ dZ, float *__restrict__ partials) {
+  const int lane = lane_id();
+  const int waves = gridDim.x * (kT / kWave);
+  float loss_acc = 0.f;  // meaningful on lane 0
+  for (int v = blockIdx.x * (kT / kWave) + threadIdx.x / kWave; v < n; v += waves) {
+    const float *z = logits + (size_t)v * C;
+    float m = -INFINITY;
+    for (int c = lane; c < C; c += kWave) m = fmaxf(m, z[c]);
+    m = wave_max(m);
+    float se = 0.f;
+    for (int c = lane; c < C; c += kWave) se += expf(z[c] - m);
+    se = wave_sum(se);
+    const int y = labels[v];
+    const float inv = 1.f / se;
+    float *g = dZ + (size_t)v * C;
+    for (int c = lane; c < C; c += kWave) g[c] = expf(z[c] - m) * inv - (c == y ? 1.f : 0.f);
+    if (lane == 0) loss_acc += (m + logf(se)) - z[y];
+  }
+  const float s = block_sum_fixed(lane == 0 ? loss_acc : 0.f);
+  if (threadIdx.x == 0) partials[blockIdx.x] = s;
+}
+
+// sigmoid binary cross-entropy over nodes x labels:
+// loss = max(z,0) - z*y + log(1 + exp(-|z|)),  dZ = sigmoid(z) - y
+__global__ void __launch_bounds__(kT)
+sigmoid_bce_kernel(int64_t total, const float *__restrict__ logits, const uint8_t *__restrict__ labels,
+                   float *__restrict__ dZ, float *__restrict__ partials) {
+  const int64_t stride = (int64_t)gridDim.x * kT;
+  float acc = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x; i < total; i += stride) {
+    const float z = logits[i];
+    const float y = (float)labels[i];
+    const float e = expf(-fabsf(z));
+    acc += fmaxf(z, 0.f) - z * y + log1pf(e);
+    const float sig = z >= 0.f ? 1.f / (1.f + e) : e / (1.f + e);
+    dZ[i] = sig - y;
+  }
+  const float s = block_sum_fixed(acc);
+  if (threadIdx.x == 0) partials[blockIdx.x] = s;
+}
+
+hipError_t loss_softmax_ce(int32_t n, int32_t C, const float *logits, const int32_t *labels,
+                           float *dZ, float *partials, float *loss, hipStream_t s) {
+  softmax_ce_kernel<<<kLossBlocks, kT, 0, s>>>(n, C, logits, labels, dZ, partials);
+  final_sum_kernel<<<1, 1024, 0, s>>>(partials, kLossBlocks, loss);
+  return hipGetLastError();
+}
+
+hipError_t loss_sigmoid_bce(int32_t n, int32_t C, const float *logits, const uint8_t *labels,
+                            float *dZ, float *partials, float *loss, hipStream_t s) {
+  sigmoid_bce_kernel<<<kLossBlocks, kT, 0, s>>>((int64_t)n * C, logits, labels, dZ, partials);
+  final_sum_kernel<<<1, 1024, 0, s>>>(partials, kLossBlocks, loss);
+  return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(kT)
+relu_mask_kernel(int64_t n, const float *__restrict__ dH, const float *__restrict__ H,
+                 float *__restrict__ out) {
+  const int64_t stride = (int64_t)gridDim.x * kT;
+  for (int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x; i < n; i += stride)
+    out[i] = H[i] > 0.f ? dH[i] : 0.f;
+}
+
+hipError_t relu_mask(int64_t n, const float *dH, const float *H, float *out, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n + kT * 4 - 1) / (kT * 4);
+  if (blocks > 65536) blocks = 65536;
+  relu_mask_kernel<<<(unsigned)blocks, kT, 0, s>>>(n, dH, H, out);
+  return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(kT)
+sgd_kernel(int64_t n, float *__restrict__ W, const float *__restrict__ dW, float lr) {
+  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i < n) W[i] -= lr * dW[i];
+}
+
+hipError_t sgd_update(int64_t n, float *W, const float *dW, float lr, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  sgd_kernel<<<(unsigned)((n + kT - 1) / kT), kT, 0, s>>>(n, W, dW, lr);
+  return hipGetLastError();
+}
+
+}  // namespace bns
