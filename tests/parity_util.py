@@ -3,9 +3,10 @@ import numpy as np
 
 RTOL = 1e-4          # max relative error (the stated bar for fp32 activations, gradients, losses)
 ABS_FLOOR = 1e-6     # absolute floor of the denominator
-RMS_FLOOR = 0.1      # elements below RMS_FLOOR * rms(reference tensor) are judged against that scale:
-                     # an fp32 sum of K terms carries an absolute error of about 6e-8 * sqrt(K) * rms
-                     # whatever the size of the (possibly cancelling) result
+RMS_FLOOR = 1.0      # elements smaller than the reference tensor's rms are judged against the rms: an
+                     # fp32 sum of K terms carries an absolute error of about 6e-8 * sqrt(K) * rms(result)
+                     # whatever the size of the (possibly cancelling) element itself
+RMS_TOL = 1e-5       # bound on rms(x - ref) / rms(ref): catches small systematic errors
 
 
 def rel_err(x, ref):
@@ -29,9 +30,20 @@ def strict_rel_err(x, ref):
     return float(np.max(np.abs(x - ref) / np.maximum(np.abs(ref), ABS_FLOOR)))
 
 
+def rms_err(x, ref):
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    den = float(np.sqrt(np.mean(ref * ref)))
+    return float(np.sqrt(np.mean((x - ref) ** 2))) / max(den, ABS_FLOOR)
+
+
 def assert_close(x, ref, what):
     e = rel_err(x, ref)
     assert e <= RTOL, f"{what}: max relative error {e:.3e} > {RTOL:g}"
+    r = rms_err(x, ref)
+    assert r <= RMS_TOL, f"{what}: rms error {r:.3e} > {RMS_TOL:g}"
     return e
 
 

@@ -8,7 +8,7 @@ Three levels per case:
   2. gcn_layer_fwd / gcn_layer_bwd fed with the ORACLE's activations, so both sides take the same
      ReLU decisions                                     -> every element within tolerance
   3. train_step end to end: integers bit-exact, forward activations and loss within tolerance;
-     its gradients agree (1e-5) with chaining the layer calls of level 2 on its own activations,
+     its gradients agree (5e-5) with chaining the layer calls of level 2 on its own activations,
      are bit-identical between two runs (no atomics), and match the oracle within tolerance
      whenever the oracle reports no pre-activation within rounding distance of zero (otherwise
      the ReLU derivative there is not unique and a looser norm-wise bound is asserted).
@@ -206,9 +206,9 @@ def test_train_step_end_to_end(case):
         dh = torch.zeros(P.n_halo + 1, d_in, **f32) if l > 1 else None
         c.ctx.gcn_layer_bwd(l, p, g, None if l == L else H_l, A_l, c.W[l - 1], dWl, dH_in, dh)
         torch.cuda.synchronize()
-        assert rel_err(dW[l - 1].cpu().numpy(), dWl.cpu().numpy()) <= 1e-5, f"dW[{l}] vs chained layers"
+        assert rel_err(dW[l - 1].cpu().numpy(), dWl.cpu().numpy()) <= 5e-5, f"dW[{l}] vs chained layers"
         if l > 1:
-            assert rel_err(dhalo[l - 1][:n_u].cpu().numpy(), dh[:n_u].cpu().numpy()) <= 1e-5, \
+            assert rel_err(dhalo[l - 1][:n_u].cpu().numpy(), dh[:n_u].cpu().numpy()) <= 5e-5, \
                 f"dhalo[{l - 1}] vs chained layers"
         g = dH_in
 
