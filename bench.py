@@ -1,0 +1,150 @@
+#!/usr/bin/env python3
+"""Benchmark of the BNS-GCN partition step on one MI355X.
+
+One "step" is one pass of the whole hot path (sample -> sampled CSR + transpose -> L layers
+forward -> loss -> backward) over one synthetic workload, with every input already resident in
+HBM.  The default workload is the largest partition share (config 5, "very-large-one-share").
+
+Prints ONE JSON line: whole-step throughput in aggregated edges/s (nnz * (2L-1) per step), the
+per-phase times measured live with HIP events, the roofline figure of the dominant kernel class
+and the CPU oracle timed on the host cores as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=5, help="config 1..5 of BASELINE.json")
+    ap.add_argument("--p", type=float, default=None, help="sampling rate (default: the config's first)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs one partition on ONE GPU; --gpus must be 1 "
+                 "(no collectives or sharding are part of it)")
+
+    import numpy as np
+    import torch
+    import paper_2203_10983_amd as pkg
+    from bns_inputs import SAMPLING_SEED, make_workload
+
+    t0 = time.time()
+    w = make_workload(args.workload)
+    P = w.part
+    p = args.p if args.p is not None else 0.1
+    L = w.n_layers
+    dev = torch.device("cuda:0")
+    ctx = pkg.Context(P, w.dims, w.loss_kind, device=dev)
+    X = torch.from_numpy(w.X).to(dev)
+    halo_h = [torch.from_numpy(h).to(dev) for h in w.halo_h]
+    labels = torch.from_numpy(w.labels).to(dev)
+    W = [torch.from_numpy(x).to(dev) for x in w.W]
+    dW = [torch.empty_like(x) for x in W]
+    dhalo = [None] + [torch.empty(P.n_halo + 1, w.dims[l], dtype=torch.float32, device=dev)
+                      for l in range(1, L)]
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    t_setup = time.time() - t0
+
+    def step(epoch):
+        ctx.train_step(SAMPLING_SEED, epoch, p, X, halo_h, labels, W, dW, dhalo, loss, 0.0)
+
+    for e in range(args.warmup):
+        step(e)
+    torch.cuda.synchronize()
+    # the timed region carries HIP-event brackets around every kernel class (10 per layer-step)
+    ctx.profile_enable(0xFFFFFFFF, args.steps * (12 * L + 8))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for e in range(args.steps):
+        step(args.warmup + e)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    phases = ctx.profile_read()
+    ctx.profile_enable(0, 0)
+
+    ms_per_step = (t2 - t1) * 1e3 / args.steps
+    n_kept = int(ctx.ws_tensor(pkg.VIEW_N_KEPT)[0])
+    nnz = int(ctx.ws_tensor(pkg.VIEW_NNZ)[0])          # of the last epoch (varies by < 1% over epochs)
+    edges_per_step = nnz * (2 * L - 1)
+    value = edges_per_step / (ms_per_step * 1e-3)
+
+    # ---- roofline of the dominant kernel class --------------------------------------------------
+    n_in, dims = P.n_in, w.dims
+    fwd_bytes = sum(4 * nnz + 4 * (n_in + 1) + 4 * dims[l - 1] * (n_in + n_kept) + 4 * dims[l - 1] * n_in
+                    for l in range(1, L + 1))
+    bwd_bytes = sum(4 * nnz + 4 * (n_in + n_kept + 1) + 4 * dims[l - 1] * n_in
+                    + 4 * dims[l - 1] * (n_in + n_kept) for l in range(2, L + 1))
+    gemm_flops = {"gemm_fwd": sum(2 * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1)),
+                  "gemm_dw": sum(2 * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1)),
+                  "gemm_da": sum(2 * n_in * dims[l - 1] * dims[l] for l in range(2, L + 1))}
+    per_step_ms = {k: v[0] / args.steps for k, v in phases.items()}
+    launches = {k: v[1] // args.steps for k, v in phases.items()}
+    cand = {k: per_step_ms[k] for k in ("spmm_fwd", "spmm_bwd", "gemm_fwd", "gemm_dw", "gemm_da")}
+    dom = max(cand, key=cand.get)
+    if dom.startswith("spmm"):
+        alg = fwd_bytes if dom == "spmm_fwd" else bwd_bytes
+        achieved = alg / (per_step_ms[dom] * 1e-3) / 1e9
+        roof = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "launches_per_step": launches[dom], "avg_launch_ms": per_step_ms[dom] / max(launches[dom], 1),
+                "algorithmic_bytes_per_step": alg}
+    else:
+        fl = gemm_flops[dom]
+        achieved = fl / (per_step_ms[dom] * 1e-3) / 1e12
+        roof = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": FP32_MFMA_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / FP32_MFMA_PEAK_TFLOPS, "traffic": None,
+                "launches_per_step": launches[dom], "avg_launch_ms": per_step_ms[dom] / max(launches[dom], 1),
+                "algorithmic_flops_per_step": fl}
+    classes = {
+        "spmm_fwd_GBps": fwd_bytes / (per_step_ms["spmm_fwd"] * 1e-3) / 1e9 if per_step_ms["spmm_fwd"] else None,
+        "spmm_bwd_GBps": bwd_bytes / (per_step_ms["spmm_bwd"] * 1e-3) / 1e9 if per_step_ms["spmm_bwd"] else None,
+    }
+    for k, fl in gemm_flops.items():
+        classes[k + "_TFLOPs"] = fl / (per_step_ms[k] * 1e-3) / 1e12 if per_step_ms[k] else None
+
+    # ---- CPU baseline: the oracle as it stands, one full step of the same workload --------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import bns_oracle as orc
+        tc = time.perf_counter()
+        ref = orc.step(P, w.loss_kind, w.X, w.halo_h, w.labels, w.W, SAMPLING_SEED, 0, p)
+        dt = time.perf_counter() - tc
+        nnz0 = int(ref["sub"]["col_idx"].size)
+        cpu = {"value": nnz0 * (2 * L - 1) / dt, "unit": "edges/s", "cores": orc.num_threads(),
+               "kind": "oracle", "sample": f"1 full step (epoch 0) of the same workload, {dt:.1f} s",
+               "ms_per_step": dt * 1e3}
+
+    out = {
+        "metric": "aggregated edges/s of one partition's BNS-GCN epoch (fwd+bwd); ms per epoch in ms_per_step",
+        "value": value, "unit": "edges/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {w.cfg}: {w.name}", "p": p, "n_in": n_in, "n_halo": P.n_halo,
+                   "n_kept": n_kept, "nnz": nnz, "dims": dims, "layers": L,
+                   "loss": "softmax_ce" if w.loss_kind == 0 else "sigmoid_bce",
+                   "edges_per_step": edges_per_step, "setup_s": round(t_setup, 1)},
+        "roofline": roof,
+        "phases_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
+        "kernel_classes": classes,
+        "sampling_overhead": (per_step_ms["sample"] + per_step_ms["build"]) / ms_per_step,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -164,6 +164,30 @@ typedef enum {
 bns_status bns_ws_view(const bns_ctx *ctx, bns_view which, int32_t layer, void **dev_ptr,
                        size_t *bytes);
 
+/* Instrumentation (no counterpart in the paper; its appendix on sampling overhead reports the
+ * share of sampling in the training time, which these timers reproduce per kernel class).
+ * While a phase's bit is set, bns_train_step and the layer calls bracket that phase's kernels
+ * with two HIP events on the call's stream.  At most max_records brackets are kept between two
+ * reads; further ones are dropped.  bns_profile_read waits for the recorded events, returns per
+ * phase the summed milliseconds and the number of brackets since the last read, and clears them.
+ * Events are host objects: no device memory is allocated. */
+typedef enum {
+  BNS_PHASE_SAMPLE = 0,   /* sample_boundary kernels                       */
+  BNS_PHASE_BUILD = 1,    /* sampled CSR + transposed CSR                  */
+  BNS_PHASE_GATHER = 2,   /* gather of kept boundary features (x 1/p)      */
+  BNS_PHASE_SPMM_FWD = 3, /* aggregate                                     */
+  BNS_PHASE_GEMM_FWD = 4, /* update  A W                                   */
+  BNS_PHASE_LOSS = 5,
+  BNS_PHASE_GEMM_DW = 6,  /* A^T dZ (split-K + reduction)                  */
+  BNS_PHASE_GEMM_DA = 7,  /* dZ W^T                                        */
+  BNS_PHASE_SPMM_BWD = 8, /* transposed aggregate                          */
+  BNS_PHASE_SGD = 9,
+  BNS_PHASE_COUNT = 10
+} bns_phase;
+bns_status bns_profile_enable(bns_ctx *ctx, uint32_t phase_mask, int32_t max_records);
+bns_status bns_profile_read(bns_ctx *ctx, double *ms_per_phase /* host [BNS_PHASE_COUNT] */,
+                            int32_t *records_per_phase /* host [BNS_PHASE_COUNT] */);
+
 #ifdef __cplusplus
 }
 #endif

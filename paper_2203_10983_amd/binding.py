@@ -17,7 +17,11 @@ LIB_PATH = os.path.join(_HERE, "libbns_gcn.so")
 
 EXPORTED = ["bns_workspace_bytes", "bns_create", "bns_destroy", "bns_last_error",
             "bns_sample_boundary", "bns_build_sampled_csr", "bns_gcn_layer_fwd",
-            "bns_gcn_layer_bwd", "bns_train_step", "bns_ws_view"]
+            "bns_gcn_layer_bwd", "bns_train_step", "bns_ws_view", "bns_profile_enable",
+            "bns_profile_read"]
+
+PHASES = ["sample", "build", "gather", "spmm_fwd", "gemm_fwd", "loss", "gemm_dw", "gemm_da",
+          "spmm_bwd", "sgd"]
 
 VIEW_KEPT_IDS, VIEW_REMAP, VIEW_N_KEPT, VIEW_ROW_PTR, VIEW_COL_IDX = 0, 1, 2, 3, 4
 VIEW_T_ROW_PTR, VIEW_T_COL_IDX, VIEW_NNZ, VIEW_A, VIEW_H = 5, 6, 7, 8, 9
@@ -79,6 +83,10 @@ def load_library():
                                  C.POINTER(vp), C.POINTER(vp), vp, C.c_float, vp]
     L.bns_ws_view.restype = i32
     L.bns_ws_view.argtypes = [vp, i32, i32, C.POINTER(vp), C.POINTER(C.c_size_t)]
+    L.bns_profile_enable.restype = i32
+    L.bns_profile_enable.argtypes = [vp, u32, i32]
+    L.bns_profile_read.restype = i32
+    L.bns_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
     _lib = L
     return L
 
@@ -172,6 +180,16 @@ class Context:
         self._check(self._lib.bns_train_step(
             self._ctx, seed, epoch, p, _ptr(X), _ptr_array(halo_h), _ptr(labels), _ptr_array(W),
             _ptr_array(dW), None if dhalo is None else _ptr_array(dhalo), _ptr(loss), lr, _stream()))
+
+    def profile_enable(self, phase_mask, max_records):
+        self._check(self._lib.bns_profile_enable(self._ctx, phase_mask, max_records))
+
+    def profile_read(self):
+        """-> {phase name: (summed ms, number of brackets)} since the last read."""
+        ms = (C.c_double * len(PHASES))()
+        cnt = (C.c_int32 * len(PHASES))()
+        self._check(self._lib.bns_profile_read(self._ctx, ms, cnt))
+        return {name: (ms[i], cnt[i]) for i, name in enumerate(PHASES)}
 
     def ws_view(self, which, layer=0):
         """Device pointer and byte size of one of bns_train_step's intermediates."""

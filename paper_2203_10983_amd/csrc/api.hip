@@ -48,7 +48,20 @@ struct Layout {
 
 }  // namespace
 
+// Optional instrumentation: HIP events around every kernel class of bns_train_step.
+struct Profiler {
+  uint32_t mask = 0;
+  std::vector<hipEvent_t> start, stop;
+  std::vector<int> phase;
+  size_t used = 0;
+  ~Profiler() {
+    for (hipEvent_t e : start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : stop) (void)hipEventDestroy(e);
+  }
+};
+
 struct bns_ctx {
+  Profiler prof;
   bns_partition_desc part;
   std::vector<int32_t> dims;
   int32_t n_layers, loss_kind;
@@ -140,6 +153,24 @@ bns_status hip_fail(bns_ctx *ctx, const char *what, hipError_t e) {
     if (_e != hipSuccess) return hip_fail(ctx, what, _e);     \
   } while (0)
 
+// Brackets the kernels enqueued during its lifetime with two events (only if the phase is enabled).
+struct PhaseTimer {
+  Profiler *p = nullptr;
+  hipStream_t s;
+  size_t slot = 0;
+  PhaseTimer(bns_ctx *ctx, int phase, hipStream_t stream) : s(stream) {
+    Profiler &pr = ctx->prof;
+    if (!((pr.mask >> phase) & 1u) || pr.used >= pr.start.size()) return;
+    p = &pr;
+    slot = pr.used++;
+    pr.phase[slot] = phase;
+    (void)hipEventRecord(pr.start[slot], s);
+  }
+  ~PhaseTimer() {
+    if (p) (void)hipEventRecord(p->stop[slot], s);
+  }
+};
+
 bool bad_p(double p) { return !(p >= 0.0 && p <= 1.0); }
 float halo_scale(double p) { return p > 0.0 ? (float)(1.0 / p) : 0.f; }  // 1/p is never formed at p = 0
 
@@ -147,11 +178,20 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
                           const float *W, float *A_saved, float *H_out, bool relu, hipStream_t s) {
   const int n_in = ctx->part.n_in, B = ctx->part.n_halo;
   const int d_in = ctx->dims[layer - 1], d_out = ctx->dims[layer];
-  BNS_TRY("halo_gather", halo_gather(halo_h, ctx->cur_kept, ctx->cur_n_kept, B, ctx->ws.dis_halo,
-                                     halo_scale(p), d_in, ctx->ws.Hu, s));
-  BNS_TRY("spmm_fwd", spmm_fwd(n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx, ctx->ws.dis_in, H_in,
-                               ctx->ws.Hu, A_saved, s));
-  BNS_TRY("gemm_nn", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, relu, s));
+  {
+    PhaseTimer t(ctx, BNS_PHASE_GATHER, s);
+    BNS_TRY("halo_gather", halo_gather(halo_h, ctx->cur_kept, ctx->cur_n_kept, B, ctx->ws.dis_halo,
+                                       halo_scale(p), d_in, ctx->ws.Hu, s));
+  }
+  {
+    PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
+    BNS_TRY("spmm_fwd", spmm_fwd(n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx, ctx->ws.dis_in, H_in,
+                                 ctx->ws.Hu, A_saved, s));
+  }
+  {
+    PhaseTimer t(ctx, BNS_PHASE_GEMM_FWD, s);
+    BNS_TRY("gemm_nn", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, relu, s));
+  }
   return BNS_OK;
 }
 
@@ -162,9 +202,16 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
                           const float *mask_src, hipStream_t s) {
   const int n_in = ctx->part.n_in, B = ctx->part.n_halo;
   const int d_in = ctx->dims[layer - 1], d_out = ctx->dims[layer];
-  BNS_TRY("gemm_tn_splitk", gemm_tn_splitk(d_in, d_out, n_in, A_saved, dZ, dW, ctx->ws.partials, s));
+  {
+    PhaseTimer t(ctx, BNS_PHASE_GEMM_DW, s);
+    BNS_TRY("gemm_tn_splitk", gemm_tn_splitk(d_in, d_out, n_in, A_saved, dZ, dW, ctx->ws.partials, s));
+  }
   if (dH_in) {
-    BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, s));
+    {
+      PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
+      BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, s));
+    }
+    PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
     BNS_TRY("spmm_bwd", spmm_bwd(n_in, B, d_in, ctx->cur_t_row_ptr, ctx->cur_t_col_idx, ctx->cur_kept,
                                  ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_halo, halo_scale(p),
                                  ctx->ws.G1, mask_src, dH_in, dhalo, s));
@@ -175,6 +222,7 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
 bns_status sample_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p, int32_t *kept_ids,
                        int32_t *remap, int32_t *n_kept, hipStream_t s) {
   const uint64_t threshold = (uint64_t)std::floor(p * 4294967296.0);
+  PhaseTimer t(ctx, BNS_PHASE_SAMPLE, s);
   BNS_TRY("sample_boundary",
           sample_boundary(ctx->part.halo_gid, ctx->part.n_halo, seed, epoch, (uint32_t)ctx->part.part_id,
                           threshold, ctx->ws.ballots, ctx->ws.tile_sums, kept_ids, remap, n_kept, s));
@@ -187,6 +235,7 @@ bns_status sample_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p, in
 bns_status build_impl(bns_ctx *ctx, int32_t *row_ptr, int32_t *col_idx, int32_t *t_row_ptr,
                       int32_t *t_col_idx, int32_t *nnz, hipStream_t s) {
   const bns_partition_desc &P = ctx->part;
+  PhaseTimer t(ctx, BNS_PHASE_BUILD, s);
   BNS_TRY("build_sampled_csr",
           build_sampled_csr(P.n_in, P.e_in, P.e_bd, ctx->ws.split, ctx->cur_remap, ctx->ws.kpos,
                             ctx->ws.tile_sums, row_ptr, col_idx, nnz, s));
@@ -320,12 +369,15 @@ bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
   }
 
   const int C = ctx->dims[L];
-  if (ctx->loss_kind == 0)
-    BNS_TRY("loss_softmax_ce", loss_softmax_ce(n_in, C, w.H[L], static_cast<const int32_t *>(labels), w.G0,
-                                               w.loss_partials, loss, s));
-  else
-    BNS_TRY("loss_sigmoid_bce", loss_sigmoid_bce(n_in, C, w.H[L], static_cast<const uint8_t *>(labels), w.G0,
+  {
+    PhaseTimer t(ctx, BNS_PHASE_LOSS, s);
+    if (ctx->loss_kind == 0)
+      BNS_TRY("loss_softmax_ce", loss_softmax_ce(n_in, C, w.H[L], static_cast<const int32_t *>(labels), w.G0,
                                                  w.loss_partials, loss, s));
+    else
+      BNS_TRY("loss_sigmoid_bce", loss_sigmoid_bce(n_in, C, w.H[L], static_cast<const uint8_t *>(labels), w.G0,
+                                                   w.loss_partials, loss, s));
+  }
 
   // G0 holds dZ of the current layer; the transposed aggregate writes the next dZ back into it,
   // masked by the activations of the layer below
@@ -335,9 +387,42 @@ bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
                         l > 1 ? w.H[l - 1] : nullptr, s);
     if (st != BNS_OK) return st;
   }
-  if (lr > 0.f)
+  if (lr > 0.f) {
+    PhaseTimer t(ctx, BNS_PHASE_SGD, s);
     for (int l = 0; l < L; ++l)
       BNS_TRY("sgd_update", sgd_update((int64_t)ctx->dims[l] * ctx->dims[l + 1], W[l], dW[l], lr, s));
+  }
+  return BNS_OK;
+}
+
+bns_status bns_profile_enable(bns_ctx *ctx, uint32_t phase_mask, int32_t max_records) {
+  if (!ctx || max_records < 0) return BNS_EINVAL;
+  Profiler &pr = ctx->prof;
+  pr.mask = phase_mask;
+  pr.used = 0;
+  while (pr.start.size() < (size_t)max_records) {
+    hipEvent_t a, b;
+    BNS_TRY("hipEventCreate", hipEventCreate(&a));
+    pr.start.push_back(a);
+    BNS_TRY("hipEventCreate", hipEventCreate(&b));
+    pr.stop.push_back(b);
+  }
+  pr.phase.assign(pr.start.size(), 0);
+  return BNS_OK;
+}
+
+bns_status bns_profile_read(bns_ctx *ctx, double *ms_per_phase, int32_t *records_per_phase) {
+  if (!ctx || !ms_per_phase || !records_per_phase) return BNS_EINVAL;
+  Profiler &pr = ctx->prof;
+  for (int i = 0; i < BNS_PHASE_COUNT; ++i) { ms_per_phase[i] = 0.0; records_per_phase[i] = 0; }
+  for (size_t k = 0; k < pr.used; ++k) {
+    BNS_TRY("hipEventSynchronize", hipEventSynchronize(pr.stop[k]));
+    float ms = 0.f;
+    BNS_TRY("hipEventElapsedTime", hipEventElapsedTime(&ms, pr.start[k], pr.stop[k]));
+    ms_per_phase[pr.phase[k]] += ms;
+    records_per_phase[pr.phase[k]] += 1;
+  }
+  pr.used = 0;
   return BNS_OK;
 }
 
