@@ -31,6 +31,9 @@ def main():
     ap.add_argument("--workload", type=int, default=5, help="config 1..5 of BASELINE.json")
     ap.add_argument("--p", type=float, default=None, help="sampling rate (default: the config's first)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device-to-device copies (a kernel of known traffic, "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs one partition on ONE GPU; --gpus must be 1 "
@@ -61,6 +64,14 @@ def main():
 
     def step(epoch):
         ctx.train_step(SAMPLING_SEED, epoch, p, X, halo_h, labels, W, dW, dhalo, loss, 0.0)
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for e in range(args.warmup):
         step(e)

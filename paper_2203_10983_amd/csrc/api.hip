@@ -40,6 +40,9 @@ struct Layout {
   uint64_t *ballots;
   int32_t *kpos, *hlen;
   float *Hu, *G0, *G1, *partials, *loss_partials;
+  SegPlan plan_f, plan_b;   // segmentation of the static CSR and of the transposed inner block
+  int32_t *seg_tmp_a, *seg_tmp_b;
+  float *spmm_partials;
   // state of bns_train_step
   int32_t *kept_ids, *remap, *counters;
   int32_t *row_ptr, *col_idx, *t_row_ptr, *t_col_idx;
@@ -121,6 +124,18 @@ size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, La
   w.G1 = c.take<float>(n_in * d_max);
   w.partials = c.take<float>(part_max);
   w.loss_partials = c.take<float>(kLossBlocks);
+  for (int k = 0; k < 2; ++k) {
+    SegPlan &pl = k == 0 ? w.plan_f : w.plan_b;
+    const int64_t nnz = k == 0 ? p->nnz0 : p->e_in;
+    pl.seg_ptr = c.take<int32_t>(n_in + 1);
+    pl.seg_row = c.take<int32_t>(seg_max_segments(n_in, nnz));
+    pl.part_ptr = c.take<int32_t>(n_in + 1);
+    pl.mrow = c.take<int32_t>(seg_max_multi(nnz));
+    pl.n_seg = pl.n_part = pl.n_multi = 0;
+  }
+  w.seg_tmp_a = c.take<int32_t>(n_in + 1);
+  w.seg_tmp_b = c.take<int32_t>(n_in + 2);
+  w.spmm_partials = c.take<float>((size_t)seg_max_parts(p->nnz0) * d_max);
   w.kept_ids = c.take<int32_t>(B + 1);
   w.remap = c.take<int32_t>(B + 1);
   w.counters = c.take<int32_t>(64);
@@ -185,8 +200,8 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
   }
   {
     PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
-    BNS_TRY("spmm_fwd", spmm_fwd(n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx, ctx->ws.dis_in, H_in,
-                                 ctx->ws.Hu, A_saved, s));
+    BNS_TRY("spmm_fwd", spmm_fwd(ctx->ws.plan_f, n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx,
+                                 ctx->ws.dis_in, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, s));
   }
   {
     PhaseTimer t(ctx, BNS_PHASE_GEMM_FWD, s);
@@ -212,9 +227,9 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
       BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, s));
     }
     PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
-    BNS_TRY("spmm_bwd", spmm_bwd(n_in, B, d_in, ctx->cur_t_row_ptr, ctx->cur_t_col_idx, ctx->cur_kept,
-                                 ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_halo, halo_scale(p),
-                                 ctx->ws.G1, mask_src, dH_in, dhalo, s));
+    BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_in, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
+                                 ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_halo,
+                                 halo_scale(p), ctx->ws.G1, mask_src, ctx->ws.spmm_partials, dH_in, dhalo, s));
   }
   return BNS_OK;
 }
@@ -285,6 +300,10 @@ bns_status bns_create(bns_ctx **out, const bns_partition_desc *part, const bns_m
   BNS_TRY("degree_rsqrt(halo)", degree_rsqrt(part->deg_halo, part->n_halo, ctx->ws.dis_halo, s));
   BNS_TRY("build_static_split", build_static_split(part->n_in, part->row_ptr0, part->col0, ctx->ws.split,
                                                    ctx->ws.tile_sums, s));
+  BNS_TRY("build_seg_plan(fwd)", build_seg_plan(part->n_in, part->row_ptr0, &ctx->ws.plan_f, ctx->ws.seg_tmp_a,
+                                                 ctx->ws.seg_tmp_b, ctx->ws.tile_sums, s));
+  BNS_TRY("build_seg_plan(bwd)", build_seg_plan(part->n_in, part->t_in_ptr, &ctx->ws.plan_b, ctx->ws.seg_tmp_a,
+                                                 ctx->ws.seg_tmp_b, ctx->ws.tile_sums, s));
   BNS_TRY("set-up sync", hipStreamSynchronize(s));
   return BNS_OK;
 }

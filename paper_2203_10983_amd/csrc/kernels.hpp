@@ -54,21 +54,43 @@ hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
                                 hipStream_t s);
 
 // ---- spmm.hip (Eq. 1 in the sampled form of Appendix A, and its transpose) ---------------------
+constexpr int kSegLen = 256;  // a wavefront aggregates at most this many neighbours
+// Static cut of the rows of a CSR pattern into segments of <= kSegLen entries (by the static row
+// lengths; a sampled row is never longer).  Upper bounds for sizing, given rows and entries:
+//   segments <= rows + nnz/kSegLen, partial slots <= 2*nnz/kSegLen, multi-segment rows <= nnz/kSegLen
+struct SegPlan {
+  int32_t *seg_ptr;   // int32[n_rows+1] first segment of each row
+  int32_t *seg_row;   // int32[n_seg]    row of each segment
+  int32_t *part_ptr;  // int32[n_rows+1] first partial-sum slot of each multi-segment row
+  int32_t *mrow;      // int32[n_multi]  rows with more than one segment
+  int32_t n_seg, n_part, n_multi;  // host copies of the totals
+};
+inline int64_t seg_max_segments(int64_t rows, int64_t nnz) { return rows + nnz / kSegLen + 1; }
+inline int64_t seg_max_parts(int64_t nnz) { return 2 * (nnz / kSegLen) + 2; }
+inline int64_t seg_max_multi(int64_t nnz) { return nnz / kSegLen + 1; }
+// Fills *plan (its arrays must be allocated to the bounds above) and waits for the stream.
+// tmp_a: scratch int32[n_rows], tmp_b: scratch int32[n_rows+1].
+hipError_t build_seg_plan(int32_t n_rows, const int32_t *row_ptr, SegPlan *plan, int32_t *tmp_a,
+                          int32_t *tmp_b, int32_t *tile_sums, hipStream_t s);
+
 // Hu[r,:] = (s_halo * dis_halo[b]) * halo_h[b,:], b = kept_ids[r], r < *n_kept.
 hipError_t halo_gather(const float *halo_h, const int32_t *kept_ids, const int32_t *n_kept,
                        int32_t n_halo, const float *dis_halo, float s_halo, int32_t d, float *Hu,
                        hipStream_t s);
 // A[v,:] = dis_in[v] * ( sum_{u<n_in in row v} dis_in[u] H_in[u,:] + sum_{kept r in row v} Hu[r,:] )
-hipError_t spmm_fwd(int32_t n_in, int32_t d, const int32_t *row_ptr, const int32_t *col_idx,
-                    const float *dis_in, const float *H_in, const float *Hu, float *A,
-                    hipStream_t s);
+// plan: segmentation of the static local CSR; partials: scratch f32[plan.n_part * d].
+hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
+                    const int32_t *col_idx, const float *dis_in, const float *H_in, const float *Hu,
+                    float *partials, float *A, hipStream_t s);
 // For stacked column u < n_in + *n_kept:  g = sum_{v in t_row u} dis_in[v] dA[v,:];
 //   u <  n_in: dH_in[u,:] = dis_in[u] * g   (zeroed where mask_src[u,:] <= 0 if mask_src != null)
 //   u >= n_in: dhalo[u-n_in,:] = s_halo * dis_halo[kept_ids[u-n_in]] * g   (skipped if dhalo null)
-hipError_t spmm_bwd(int32_t n_in, int32_t n_halo, int32_t d, const int32_t *t_row_ptr,
-                    const int32_t *t_col_idx, const int32_t *kept_ids, const int32_t *n_kept,
-                    const float *dis_in, const float *dis_halo, float s_halo, const float *dA,
-                    const float *mask_src, float *dH_in, float *dhalo, hipStream_t s);
+// plan: segmentation of the transposed inner-inner block (rows of kept boundary nodes are short).
+hipError_t spmm_bwd(const SegPlan &plan, int32_t n_in, int32_t n_halo, int32_t d,
+                    const int32_t *t_row_ptr, const int32_t *t_col_idx, const int32_t *kept_ids,
+                    const int32_t *n_kept, const float *dis_in, const float *dis_halo, float s_halo,
+                    const float *dA, const float *mask_src, float *partials, float *dH_in,
+                    float *dhalo, hipStream_t s);
 
 // ---- gemm.hip (Eq. 2 and its backward; fp32 MFMA) ----------------------------------------------
 // C[M,N] = A[M,K] B[K,N], optional ReLU.
@@ -84,7 +106,7 @@ hipError_t gemm_tn_splitk(int32_t M, int32_t N, int32_t K, const float *A, const
                           float *C, float *partials, hipStream_t s);
 
 // ---- loss.hip (Algorithm 1, loss step) ---------------------------------------------------------
-constexpr int kLossBlocks = 1024;  // partials: scratch f32[kLossBlocks]
+constexpr int kLossBlocks = 8192;  // partials: scratch f32[kLossBlocks]
 hipError_t loss_softmax_ce(int32_t n, int32_t C, const float *logits, const int32_t *labels,
                            float *dZ, float *partials, float *loss, hipStream_t s);
 hipError_t loss_sigmoid_bce(int32_t n, int32_t C, const float *logits, const uint8_t *labels,

@@ -38,7 +38,7 @@ final_sum_kernel(const float *__restrict__ partials, int n, float *__restrict__ 
 }
 
 // softmax cross-entropy: one wavefront per node; loss_v = logsumexp(z_v) - z_v[y_v],
-// dZ_v = softmax(z_v) - onehot(y_v)
+// dZ_v = softmax(z_v) - onehot(y_v).  Up to 256 classes a row lives in registers (one read).
 __global__ void __launch_bounds__(kT)
 softmax_ce_kernel(int n, int C, const float *__restrict__ logits, const int32_t *__restrict__ labels,
                   float *__restrict__ dZ, float *__restrict__ partials) {
@@ -47,17 +47,43 @@ softmax_ce_kernel(int n, int C, const float *__restrict__ logits, const int32_t 
   float loss_acc = 0.f;  // meaningful on lane 0
   for (int v = blockIdx.x * (kT / kWave) + threadIdx.x / kWave; v < n; v += waves) {
     const float *z = logits + (size_t)v * C;
-    float m = -INFINITY;
-    for (int c = lane; c < C; c += kWave) m = fmaxf(m, z[c]);
-    m = wave_max(m);
-    float se = 0.f;
-    for (int c = lane; c < C; c += kWave) se += expf(z[c] - m);
-    se = wave_sum(se);
-    const int y = labels[v];
-    const float inv = 1.f / se;
     float *g = dZ + (size_t)v * C;
-    for (int c = lane; c < C; c += kWave) g[c] = expf(z[c] - m) * inv - (c == y ? 1.f : 0.f);
-    if (lane == 0) loss_acc += (m + logf(se)) - z[y];
+    const int y = labels[v];
+    if (C <= 4 * kWave) {
+      float x[4];
+      float m = -INFINITY;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int c = lane + k * kWave;
+        x[k] = c < C ? z[c] : -INFINITY;
+        m = fmaxf(m, x[k]);
+      }
+      m = wave_max(m);
+      float se = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        x[k] = lane + k * kWave < C ? expf(x[k] - m) : 0.f;
+        se += x[k];
+      }
+      se = wave_sum(se);
+      const float inv = 1.f / se;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int c = lane + k * kWave;
+        if (c < C) g[c] = x[k] * inv - (c == y ? 1.f : 0.f);
+      }
+      if (lane == 0) loss_acc += (m + logf(se)) - z[y];
+    } else {
+      float m = -INFINITY;
+      for (int c = lane; c < C; c += kWave) m = fmaxf(m, z[c]);
+      m = wave_max(m);
+      float se = 0.f;
+      for (int c = lane; c < C; c += kWave) se += expf(z[c] - m);
+      se = wave_sum(se);
+      const float inv = 1.f / se;
+      for (int c = lane; c < C; c += kWave) g[c] = expf(z[c] - m) * inv - (c == y ? 1.f : 0.f);
+      if (lane == 0) loss_acc += (m + logf(se)) - z[y];
+    }
   }
   const float s = block_sum_fixed(lane == 0 ? loss_acc : 0.f);
   if (threadIdx.x == 0) partials[blockIdx.x] = s;

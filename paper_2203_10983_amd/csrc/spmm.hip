@@ -1,12 +1,17 @@
 // Sparse aggregate (Eq. 1 in the sampled matrix form of Appendix A) and its transpose.
 //
-// One 64-lane wavefront owns one output row.  The lanes span the feature dimension with
-// VEC-wide loads, so every neighbour row is read as one contiguous, coalesced segment.  When a
-// feature row needs fewer than 64 lanes (LPR = lanes per row < 64) the wavefront walks 64/LPR
-// neighbours at once and folds the partial sums at the end.  Column indices and their weights
-// are fetched 64 at a time, one per lane, and handed to the loop by cross-lane reads, four
-// neighbours in flight per step.  No atomics: the backward pass walks the transposed pattern,
-// so every output element is produced by exactly one lane in a fixed order.
+// Work unit: one 64-lane wavefront owns one SEGMENT of an output row, at most kSegLen
+// neighbours.  Power-law graphs put a large share of all edges into a few very long rows; cutting
+// every row into bounded segments keeps the wavefronts balanced.  A row with one segment is
+// finished by its wavefront; a row with several gets one partial sum per segment, and a second
+// small kernel adds them in ascending order.  No atomics anywhere: the backward pass walks the
+// transposed pattern, and every output element is produced in a fixed order.
+//
+// Inside a segment the lanes span the feature dimension with VEC-wide loads, so every neighbour
+// row is read as one contiguous, coalesced piece.  When a feature row needs fewer than 64 lanes
+// (LPR = lanes per row < 64) the wavefront walks 64/LPR neighbours at once and folds the partial
+// sums at the end.  Column indices and their weights are fetched 64 at a time, one per lane,
+// and handed to the loop by cross-lane reads, four neighbours in flight per step.
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -25,12 +30,13 @@ __device__ __forceinline__ void vec_fma(float (&acc)[VEC], float w, const typena
 }
 
 struct SpmmArgs {
-  int32_t n_rows_static;       // rows when n_extra_dev == nullptr
-  const int32_t *n_extra_dev;  // rows = n_rows_static + *n_extra_dev (transposed pass)
+  SegPlan plan;                // static segmentation of rows 0..n_split-1
+  const int32_t *n_extra_dev;  // nullable: *n_extra_dev further single-segment rows follow (kept boundary)
   int32_t d;
   const int32_t *row_ptr, *col_idx;
   int32_t n_split;             // columns < n_split read src0 (weight w_col[c]); others src1 (weight 1)
   const float *src0, *src1, *w_col;
+  float *partials;             // one d-vector per segment of multi-segment rows
   // output rows < n_split: out0 (scale out_scale0[row], optional mask); others: out1
   float *out0, *out1;
   const float *out_scale0;
@@ -40,6 +46,44 @@ struct SpmmArgs {
   float s_halo;
 };
 
+// Scale, optional ReLU mask and store of one finished row slice held as acc[c][i].
+template <int VEC, int MAXCH>
+__device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, int nvec,
+                                           float (&acc)[MAXCH][VEC]) {
+  using V = typename Vec<VEC>::T;
+  const int d = a.d;
+  float scale;
+  float *out;
+  const float *mask = nullptr;
+  if (row < a.n_split) {
+    scale = a.out_scale0[row];
+    out = a.out0 + (size_t)row * d;
+    if (a.mask_src) mask = a.mask_src + (size_t)row * d;
+  } else {
+    if (a.out1 == nullptr) return;
+    const int r = row - a.n_split;
+    scale = a.s_halo * a.dis_halo[a.kept_ids[r]];
+    out = a.out1 + (size_t)r * d;
+  }
+#pragma unroll
+  for (int c = 0; c < MAXCH; ++c) {
+    const int iv = c * kWave + sl;
+    if (iv < nvec) {
+      V o;
+      float *po = reinterpret_cast<float *>(&o);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) po[i] = acc[c][i] * scale;
+      if (mask) {
+        const V m = reinterpret_cast<const V *>(mask)[iv];
+        const float *pm = reinterpret_cast<const float *>(&m);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) po[i] = pm[i] > 0.f ? po[i] : 0.f;
+      }
+      reinterpret_cast<V *>(out)[iv] = o;
+    }
+  }
+}
+
 template <int VEC, int MAXCH, int LPR>
 __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
   using V = typename Vec<VEC>::T;
@@ -47,11 +91,27 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
   constexpr int UNR = 4;
   const int lane = lane_id();
   const int g = lane / LPR, sl = lane % LPR;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int n_rows = a.n_rows_static + (a.n_extra_dev ? *a.n_extra_dev : 0);
-  if (row >= n_rows) return;
+  const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int d = a.d;
   const int nvec = d / VEC;
+
+  int row, seg = 0, nseg = 1;
+  if (unit < a.plan.n_seg) {
+    row = a.plan.seg_row[unit];
+    const int s0 = a.plan.seg_ptr[row];
+    seg = unit - s0;
+    nseg = a.plan.seg_ptr[row + 1] - s0;
+  } else {
+    const int r = unit - a.plan.n_seg;
+    if (a.n_extra_dev == nullptr || r >= *a.n_extra_dev) return;
+    row = a.n_split + r;
+  }
+  int e0 = a.row_ptr[row], e1 = a.row_ptr[row + 1];
+  if (nseg > 1) {  // this wavefront's slice of the row as it is in this epoch
+    const int chunk = (e1 - e0 + nseg - 1) / nseg;
+    e0 = min(e1, e0 + seg * chunk);
+    e1 = min(e1, e0 + chunk);
+  }
 
   float acc[MAXCH][VEC];
 #pragma unroll
@@ -59,7 +119,6 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
 
-  const int e0 = a.row_ptr[row], e1 = a.row_ptr[row + 1];
   for (int base = e0; base < e1; base += kWave) {
     const int cnt = min(kWave, e1 - base);
     // one neighbour per lane: its feature-row address and weight
@@ -119,44 +178,67 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
     if (g != 0) return;
   }
 
-  float scale;
-  float *out;
-  const float *mask = nullptr;
-  if (row < a.n_split) {
-    scale = a.out_scale0[row];
-    out = a.out0 + (size_t)row * d;
-    if (a.mask_src) mask = a.mask_src + (size_t)row * d;
+  if (nseg == 1) {
+    finish_row<VEC, MAXCH>(a, row, sl, nvec, acc);
   } else {
-    if (a.out1 == nullptr) return;
-    const int r = row - a.n_split;
-    scale = a.s_halo * a.dis_halo[a.kept_ids[r]];
-    out = a.out1 + (size_t)r * d;
-  }
+    V *part = reinterpret_cast<V *>(a.partials + (size_t)(a.plan.part_ptr[row] + seg) * d);
 #pragma unroll
-  for (int c = 0; c < MAXCH; ++c) {
-    const int iv = c * kWave + sl;
-    if (iv < nvec) {
-      V o;
-      float *po = reinterpret_cast<float *>(&o);
+    for (int c = 0; c < MAXCH; ++c) {
+      const int iv = c * kWave + sl;
+      if (iv < nvec) {
+        V o;
+        float *po = reinterpret_cast<float *>(&o);
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) po[i] = acc[c][i] * scale;
-      if (mask) {
-        const V m = reinterpret_cast<const V *>(mask)[iv];
-        const float *pm = reinterpret_cast<const float *>(&m);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) po[i] = pm[i] > 0.f ? po[i] : 0.f;
+        for (int i = 0; i < VEC; ++i) po[i] = acc[c][i];
+        part[iv] = o;
       }
-      reinterpret_cast<V *>(out)[iv] = o;
     }
   }
 }
 
+// Rows cut into several segments: add the partial sums in ascending segment order.
+template <int VEC, int MAXCH>
+__global__ void __launch_bounds__(256) spmm_combine_kernel(const SpmmArgs a) {
+  using V = typename Vec<VEC>::T;
+  const int lane = lane_id();
+  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (j >= a.plan.n_multi) return;
+  const int row = a.plan.mrow[j];
+  const int nseg = a.plan.seg_ptr[row + 1] - a.plan.seg_ptr[row];
+  const int d = a.d, nvec = d / VEC;
+  const float *part = a.partials + (size_t)a.plan.part_ptr[row] * d;
+  float acc[MAXCH][VEC];
+#pragma unroll
+  for (int c = 0; c < MAXCH; ++c)
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
+  for (int s = 0; s < nseg; ++s) {
+    const V *ps = reinterpret_cast<const V *>(part + (size_t)s * d);
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c) {
+      const int iv = c * kWave + lane;
+      if (iv < nvec) {
+        const V x = ps[iv];
+        const float *px = reinterpret_cast<const float *>(&x);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[c][i] += px[i];
+      }
+    }
+  }
+  finish_row<VEC, MAXCH>(a, row, lane, nvec, acc);
+}
+
 template <int VEC>
-static hipError_t launch_spmm_vec(const SpmmArgs &a, int64_t max_rows, hipStream_t s) {
+static hipError_t launch_spmm_vec(const SpmmArgs &a, int64_t max_units, hipStream_t s) {
   const int nvec = a.d / VEC;
-  const unsigned blocks = (unsigned)((max_rows + 3) / 4);
+  const unsigned blocks = (unsigned)((max_units + 3) / 4);
+  const unsigned cblocks = (unsigned)((a.plan.n_multi + 3) / 4);
   if (blocks == 0) return hipSuccess;
-#define BNS_SPMM(MAXCH, LPR) spmm_kernel<VEC, MAXCH, LPR><<<blocks, 256, 0, s>>>(a)
+#define BNS_SPMM(MAXCH, LPR)                                                        \
+  do {                                                                              \
+    spmm_kernel<VEC, MAXCH, LPR><<<blocks, 256, 0, s>>>(a);                         \
+    if (cblocks) spmm_combine_kernel<VEC, MAXCH><<<cblocks, 256, 0, s>>>(a);        \
+  } while (0)
   if (nvec <= 1) BNS_SPMM(1, 1);
   else if (nvec <= 2) BNS_SPMM(1, 2);
   else if (nvec <= 4) BNS_SPMM(1, 4);
@@ -173,36 +255,97 @@ static hipError_t launch_spmm_vec(const SpmmArgs &a, int64_t max_rows, hipStream
   return hipGetLastError();
 }
 
-static hipError_t launch_spmm(const SpmmArgs &a, int64_t max_rows, hipStream_t s) {
-  if (a.d % 4 == 0) return launch_spmm_vec<4>(a, max_rows, s);
-  if (a.d % 2 == 0) return launch_spmm_vec<2>(a, max_rows, s);
-  return launch_spmm_vec<1>(a, max_rows, s);
+static hipError_t launch_spmm(const SpmmArgs &a, int64_t max_units, hipStream_t s) {
+  if (a.d % 4 == 0) return launch_spmm_vec<4>(a, max_units, s);
+  if (a.d % 2 == 0) return launch_spmm_vec<2>(a, max_units, s);
+  return launch_spmm_vec<1>(a, max_units, s);
 }
 
-hipError_t spmm_fwd(int32_t n_in, int32_t d, const int32_t *row_ptr, const int32_t *col_idx,
-                    const float *dis_in, const float *H_in, const float *Hu, float *A,
-                    hipStream_t s) {
+hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
+                    const int32_t *col_idx, const float *dis_in, const float *H_in, const float *Hu,
+                    float *partials, float *A, hipStream_t s) {
   SpmmArgs a{};
-  a.n_rows_static = n_in; a.n_extra_dev = nullptr; a.d = d;
+  a.plan = plan; a.n_extra_dev = nullptr; a.d = d;
   a.row_ptr = row_ptr; a.col_idx = col_idx; a.n_split = n_in;
-  a.src0 = H_in; a.src1 = Hu; a.w_col = dis_in;
+  a.src0 = H_in; a.src1 = Hu; a.w_col = dis_in; a.partials = partials;
   a.out0 = A; a.out1 = nullptr; a.out_scale0 = dis_in; a.mask_src = nullptr;
   a.kept_ids = nullptr; a.dis_halo = nullptr; a.s_halo = 0.f;
-  return launch_spmm(a, n_in, s);
+  return launch_spmm(a, plan.n_seg, s);
 }
 
-hipError_t spmm_bwd(int32_t n_in, int32_t n_halo, int32_t d, const int32_t *t_row_ptr,
-                    const int32_t *t_col_idx, const int32_t *kept_ids, const int32_t *n_kept,
-                    const float *dis_in, const float *dis_halo, float s_halo, const float *dA,
-                    const float *mask_src, float *dH_in, float *dhalo, hipStream_t s) {
+hipError_t spmm_bwd(const SegPlan &plan, int32_t n_in, int32_t n_halo, int32_t d,
+                    const int32_t *t_row_ptr, const int32_t *t_col_idx, const int32_t *kept_ids,
+                    const int32_t *n_kept, const float *dis_in, const float *dis_halo, float s_halo,
+                    const float *dA, const float *mask_src, float *partials, float *dH_in,
+                    float *dhalo, hipStream_t s) {
   SpmmArgs a{};
-  a.n_rows_static = n_in; a.n_extra_dev = (dhalo && n_halo > 0) ? n_kept : nullptr; a.d = d;
+  const bool halo_rows = dhalo && n_halo > 0;
+  a.plan = plan; a.n_extra_dev = halo_rows ? n_kept : nullptr; a.d = d;
   a.row_ptr = t_row_ptr; a.col_idx = t_col_idx; a.n_split = n_in;
-  a.src0 = dA; a.src1 = nullptr; a.w_col = dis_in;
+  a.src0 = dA; a.src1 = nullptr; a.w_col = dis_in; a.partials = partials;
   a.out0 = dH_in; a.out1 = dhalo; a.out_scale0 = dis_in; a.mask_src = mask_src;
   a.kept_ids = kept_ids; a.dis_halo = dis_halo; a.s_halo = s_halo;
-  const int64_t max_rows = (int64_t)n_in + ((dhalo && n_halo > 0) ? n_halo : 0);
-  return launch_spmm(a, max_rows, s);
+  return launch_spmm(a, (int64_t)plan.n_seg + (halo_rows ? n_halo : 0), s);
+}
+
+// ------------------------------------------------------------------------------------------
+// Static segmentation of a CSR pattern (set-up).
+__global__ void __launch_bounds__(256)
+seg_count_kernel(int32_t n_rows, const int32_t *__restrict__ row_ptr, int32_t *__restrict__ nseg) {
+  const int v = blockIdx.x * 256 + threadIdx.x;
+  if (v >= n_rows) return;
+  const int len = row_ptr[v + 1] - row_ptr[v];
+  nseg[v] = len <= kSegLen ? 1 : (len + kSegLen - 1) / kSegLen;
+}
+
+// which: 0 -> number of partial slots of the row (0 for single-segment rows), 1 -> multi flag
+__global__ void __launch_bounds__(256)
+seg_multi_kernel(int32_t n_rows, const int32_t *__restrict__ seg_ptr, int which, int32_t *__restrict__ out) {
+  const int v = blockIdx.x * 256 + threadIdx.x;
+  if (v >= n_rows) return;
+  const int n = seg_ptr[v + 1] - seg_ptr[v];
+  out[v] = n > 1 ? (which == 0 ? n : 1) : 0;
+}
+
+__global__ void __launch_bounds__(256)
+seg_fill_kernel(int32_t n_rows, const int32_t *__restrict__ seg_ptr, const int32_t *__restrict__ mpos,
+                int32_t *__restrict__ seg_row, int32_t *__restrict__ mrow) {
+  const int v = blockIdx.x * 256 + threadIdx.x;
+  if (v >= n_rows) return;
+  const int s0 = seg_ptr[v], s1 = seg_ptr[v + 1];
+  for (int s = s0; s < s1; ++s) seg_row[s] = v;
+  if (s1 - s0 > 1) mrow[mpos[v]] = v;
+}
+
+hipError_t build_seg_plan(int32_t n_rows, const int32_t *row_ptr, SegPlan *plan, int32_t *tmp_a,
+                          int32_t *tmp_b, int32_t *tile_sums, hipStream_t s) {
+  const unsigned blocks = (unsigned)((n_rows + 255) / 256);
+  seg_count_kernel<<<blocks, 256, 0, s>>>(n_rows, row_ptr, tmp_a);
+  hipError_t e = scan_exclusive_i32(tmp_a, plan->seg_ptr, n_rows, nullptr, tile_sums, nullptr, 0, s);
+  if (e != hipSuccess) return e;
+  seg_multi_kernel<<<blocks, 256, 0, s>>>(n_rows, plan->seg_ptr, 0, tmp_a);
+  e = scan_exclusive_i32(tmp_a, plan->part_ptr, n_rows, nullptr, tile_sums, nullptr, 0, s);
+  if (e != hipSuccess) return e;
+  seg_multi_kernel<<<blocks, 256, 0, s>>>(n_rows, plan->seg_ptr, 1, tmp_a);
+  e = scan_exclusive_i32(tmp_a, tmp_b, n_rows, nullptr, tile_sums, nullptr, 0, s);
+  if (e != hipSuccess) return e;
+  seg_fill_kernel<<<blocks, 256, 0, s>>>(n_rows, plan->seg_ptr, tmp_b, plan->seg_row, plan->mrow);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // the three totals size the launches: bring them to the host (set-up only)
+  int32_t tot[3];
+  e = hipMemcpyAsync(&tot[0], plan->seg_ptr + n_rows, 4, hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return e;
+  e = hipMemcpyAsync(&tot[1], plan->part_ptr + n_rows, 4, hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return e;
+  e = hipMemcpyAsync(&tot[2], tmp_b + n_rows, 4, hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return e;
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return e;
+  plan->n_seg = tot[0];
+  plan->n_part = tot[1];
+  plan->n_multi = tot[2];
+  return hipSuccess;
 }
 
 // ------------------------------------------------------------------------------------------
