@@ -69,7 +69,7 @@ def main():
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            torch.add(src, 1.0, out=dst)        # one elementwise kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del src, dst
 
@@ -120,6 +120,15 @@ def main():
                 "unit": "TFLOP/s", "frac": achieved / FP32_MFMA_PEAK_TFLOPS, "traffic": None,
                 "launches_per_step": launches[dom], "avg_launch_ms": per_step_ms[dom] / max(launches[dom], 1),
                 "algorithmic_flops_per_step": fl}
+    # HBM-side bytes per launch from the committed rocprofv3 PMC run of this workload, if there is one
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
+            tr = json.load(fh)
+        if tr["workload"].startswith(f"config {w.cfg}:") and abs(tr["p"] - p) < 1e-12:
+            roof["traffic"] = tr["bytes_per_launch"].get(dom.split("_")[0])
+            roof["traffic_source"] = tr["source"]
+    except (OSError, KeyError, ValueError):
+        pass
     classes = {
         "spmm_fwd_GBps": fwd_bytes / (per_step_ms["spmm_fwd"] * 1e-3) / 1e9 if per_step_ms["spmm_fwd"] else None,
         "spmm_bwd_GBps": bwd_bytes / (per_step_ms["spmm_bwd"] * 1e-3) / 1e9 if per_step_ms["spmm_bwd"] else None,

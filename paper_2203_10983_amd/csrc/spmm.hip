@@ -12,6 +12,9 @@
 // (LPR = lanes per row < 64) the wavefront walks 64/LPR neighbours at once and folds the partial
 // sums at the end.  Column indices and their weights are fetched 64 at a time, one per lane,
 // and handed to the loop by cross-lane reads, four neighbours in flight per step.
+#include <algorithm>
+#include <cstdlib>
+
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -91,10 +94,11 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
   constexpr int UNR = 4;
   const int lane = lane_id();
   const int g = lane / LPR, sl = lane % LPR;
-  const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int d = a.d;
   const int nvec = d / VEC;
-
+  // work units: the static segments, then one unit per kept boundary row (count on the device)
+  const int n_units = a.plan.n_seg + (a.n_extra_dev ? *a.n_extra_dev : 0);
+  for (int unit = blockIdx.x * 4 + (threadIdx.x >> 6); unit < n_units; unit += gridDim.x * 4) {
   int row, seg = 0, nseg = 1;
   if (unit < a.plan.n_seg) {
     row = a.plan.seg_row[unit];
@@ -102,9 +106,7 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
     seg = unit - s0;
     nseg = a.plan.seg_ptr[row + 1] - s0;
   } else {
-    const int r = unit - a.plan.n_seg;
-    if (a.n_extra_dev == nullptr || r >= *a.n_extra_dev) return;
-    row = a.n_split + r;
+    row = a.n_split + (unit - a.plan.n_seg);
   }
   int e0 = a.row_ptr[row], e1 = a.row_ptr[row + 1];
   if (nseg > 1) {  // this wavefront's slice of the row as it is in this epoch
@@ -175,10 +177,11 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
     for (int off = LPR; off < kWave; off <<= 1)
 #pragma unroll
       for (int i = 0; i < VEC; ++i) acc[0][i] += __shfl_xor(acc[0][i], off, kWave);
-    if (g != 0) return;
   }
 
-  if (nseg == 1) {
+  if (g != 0) {
+    // only the first lane group holds the folded sums
+  } else if (nseg == 1) {
     finish_row<VEC, MAXCH>(a, row, sl, nvec, acc);
   } else {
     V *part = reinterpret_cast<V *>(a.partials + (size_t)(a.plan.part_ptr[row] + seg) * d);
@@ -194,6 +197,7 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
       }
     }
   }
+  }  // unit loop
 }
 
 // Rows cut into several segments: add the partial sums in ascending segment order.
@@ -212,18 +216,26 @@ __global__ void __launch_bounds__(256) spmm_combine_kernel(const SpmmArgs a) {
   for (int c = 0; c < MAXCH; ++c)
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
-  for (int s = 0; s < nseg; ++s) {
-    const V *ps = reinterpret_cast<const V *>(part + (size_t)s * d);
+  constexpr int CU = 8;  // partial vectors fetched together; they are still added in ascending order
+  for (int s0 = 0; s0 < nseg; s0 += CU) {
+    V x[CU][MAXCH];
 #pragma unroll
-    for (int c = 0; c < MAXCH; ++c) {
-      const int iv = c * kWave + lane;
-      if (iv < nvec) {
-        const V x = ps[iv];
-        const float *px = reinterpret_cast<const float *>(&x);
+    for (int t = 0; t < CU; ++t) {
+      const V *ps = reinterpret_cast<const V *>(part + (size_t)(s0 + t) * d);
+#pragma unroll
+      for (int c = 0; c < MAXCH; ++c) {
+        const int iv = c * kWave + lane;
+        x[t][c] = (s0 + t < nseg && iv < nvec) ? ps[iv] : V{};
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < CU; ++t)
+#pragma unroll
+      for (int c = 0; c < MAXCH; ++c) {
+        const float *px = reinterpret_cast<const float *>(&x[t][c]);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[c][i] += px[i];
       }
-    }
   }
   finish_row<VEC, MAXCH>(a, row, lane, nvec, acc);
 }
@@ -231,7 +243,12 @@ __global__ void __launch_bounds__(256) spmm_combine_kernel(const SpmmArgs a) {
 template <int VEC>
 static hipError_t launch_spmm_vec(const SpmmArgs &a, int64_t max_units, hipStream_t s) {
   const int nvec = a.d / VEC;
-  const unsigned blocks = (unsigned)((max_units + 3) / 4);
+  // one wavefront per static segment; the kept boundary rows, whose count lives on the device,
+  // are strided over by a bounded number of extra blocks (blocks past the count would only cost
+  // dispatch time)
+  const int64_t seg_blocks = ((int64_t)a.plan.n_seg + 3) / 4;
+  const int64_t extra_blocks = std::min<int64_t>((max_units - a.plan.n_seg + 3) / 4, 8192);
+  const unsigned blocks = (unsigned)(seg_blocks + std::max<int64_t>(extra_blocks, 0));
   const unsigned cblocks = (unsigned)((a.plan.n_multi + 3) / 4);
   if (blocks == 0) return hipSuccess;
 #define BNS_SPMM(MAXCH, LPR)                                                        \
