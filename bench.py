@@ -31,6 +31,8 @@ def main():
     ap.add_argument("--workload", type=int, default=5, help="config 1..5 of BASELINE.json")
     ap.add_argument("--p", type=float, default=None, help="sampling rate (default: the config's first)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-input-cache", action="store_true",
+                    help="do not install the static inner aggregate of layer 1 (bns_cache_input_aggregate)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies (a kernel of known traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -73,6 +75,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if not args.no_input_cache:
+        ctx.cache_input_aggregate(X)      # one-off, outside the timed region: X is the same every epoch
     for e in range(args.warmup):
         step(e)
     torch.cuda.synchronize()
@@ -97,6 +101,10 @@ def main():
     n_in, dims = P.n_in, w.dims
     fwd_bytes = sum(4 * nnz + 4 * (n_in + 1) + 4 * dims[l - 1] * (n_in + n_kept) + 4 * dims[l - 1] * n_in
                     for l in range(1, L + 1))
+    if not args.no_input_cache:
+        # layer 1 reads the cached inner sum and the kept boundary rows instead of all neighbours
+        e_u = nnz - P.e_in
+        fwd_bytes += -(4 * nnz + 4 * dims[0] * (n_in + n_kept)) + 4 * e_u + 4 * dims[0] * (n_in + n_kept)
     bwd_bytes = sum(4 * nnz + 4 * (n_in + n_kept + 1) + 4 * dims[l - 1] * n_in
                     + 4 * dims[l - 1] * (n_in + n_kept) for l in range(2, L + 1))
     gemm_flops = {"gemm_fwd": sum(2 * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1)),
@@ -156,7 +164,8 @@ def main():
         "config": {"workload": f"config {w.cfg}: {w.name}", "p": p, "n_in": n_in, "n_halo": P.n_halo,
                    "n_kept": n_kept, "nnz": nnz, "dims": dims, "layers": L,
                    "loss": "softmax_ce" if w.loss_kind == 0 else "sigmoid_bce",
-                   "edges_per_step": edges_per_step, "setup_s": round(t_setup, 1)},
+                   "edges_per_step": edges_per_step, "setup_s": round(t_setup, 1),
+                   "input_aggregate_cached": not args.no_input_cache},
         "roofline": roof,
         "phases_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
         "kernel_classes": classes,

@@ -148,6 +148,14 @@ bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
                           float *const *dW, float *const *dhalo, float *loss, float lr,
                           void *stream);
 
+/* Static-inner caching.  The input features X and the inner-inner edges are the same in every
+ * epoch; sampling only changes the boundary entries of a row (Appendix D).  This call aggregates the
+ * inner neighbours of layer 1 once, C[v,:] = sum_{u in V_i, u ~ v} d~_u^-1/2 X[u,:], into the
+ * workspace.  Afterwards every layer-1 forward whose input pointer equals X (bns_gcn_layer_fwd with
+ * layer 1, bns_train_step) aggregates only the kept boundary tail of each row and adds C.  The caller
+ * promises not to change the contents of X while the cache is installed; X = NULL drops it. */
+bns_status bns_cache_input_aggregate(bns_ctx *ctx, const float *X /* dev f32[n_in*d_0] */, void *stream);
+
 /* Where bns_train_step keeps its intermediates inside the workspace (for inspection). */
 typedef enum {
   BNS_VIEW_KEPT_IDS = 0,  /* int32[n_halo]            */

@@ -17,8 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libbns_gcn.so")
 
 EXPORTED = ["bns_workspace_bytes", "bns_create", "bns_destroy", "bns_last_error",
             "bns_sample_boundary", "bns_build_sampled_csr", "bns_gcn_layer_fwd",
-            "bns_gcn_layer_bwd", "bns_train_step", "bns_ws_view", "bns_profile_enable",
-            "bns_profile_read"]
+            "bns_gcn_layer_bwd", "bns_train_step", "bns_cache_input_aggregate", "bns_ws_view",
+            "bns_profile_enable", "bns_profile_read"]
 
 PHASES = ["sample", "build", "gather", "spmm_fwd", "gemm_fwd", "loss", "gemm_dw", "gemm_da",
           "spmm_bwd", "sgd"]
@@ -81,6 +81,8 @@ def load_library():
     L.bns_train_step.restype = i32
     L.bns_train_step.argtypes = [vp, u64, u32, f64, vp, C.POINTER(vp), vp, C.POINTER(vp),
                                  C.POINTER(vp), C.POINTER(vp), vp, C.c_float, vp]
+    L.bns_cache_input_aggregate.restype = i32
+    L.bns_cache_input_aggregate.argtypes = [vp, vp, vp]
     L.bns_ws_view.restype = i32
     L.bns_ws_view.argtypes = [vp, i32, i32, C.POINTER(vp), C.POINTER(C.c_size_t)]
     L.bns_profile_enable.restype = i32
@@ -180,6 +182,9 @@ class Context:
         self._check(self._lib.bns_train_step(
             self._ctx, seed, epoch, p, _ptr(X), _ptr_array(halo_h), _ptr(labels), _ptr_array(W),
             _ptr_array(dW), None if dhalo is None else _ptr_array(dhalo), _ptr(loss), lr, _stream()))
+
+    def cache_input_aggregate(self, X):
+        self._check(self._lib.bns_cache_input_aggregate(self._ctx, _ptr(X), _stream()))
 
     def profile_enable(self, phase_mask, max_records):
         self._check(self._lib.bns_profile_enable(self._ctx, phase_mask, max_records))

@@ -43,6 +43,7 @@ struct Layout {
   SegPlan plan_f, plan_b;   // segmentation of the static CSR and of the transposed inner block
   int32_t *seg_tmp_a, *seg_tmp_b;
   float *spmm_partials;
+  float *C0;                // cached inner part of layer 1's aggregate (n_in x d_0)
   // state of bns_train_step
   int32_t *kept_ids, *remap, *counters;
   int32_t *row_ptr, *col_idx, *t_row_ptr, *t_col_idx;
@@ -73,6 +74,7 @@ struct bns_ctx {
   const int32_t *cur_kept = nullptr, *cur_remap = nullptr, *cur_n_kept = nullptr;
   const int32_t *cur_row_ptr = nullptr, *cur_col_idx = nullptr, *cur_t_row_ptr = nullptr,
                 *cur_t_col_idx = nullptr;
+  const float *cache_X = nullptr;  // features whose inner aggregate sits in ws.C0 (nullptr: none)
   std::string err;
 };
 
@@ -136,6 +138,7 @@ size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, La
   w.seg_tmp_a = c.take<int32_t>(n_in + 1);
   w.seg_tmp_b = c.take<int32_t>(n_in + 2);
   w.spmm_partials = c.take<float>((size_t)seg_max_parts(p->nnz0) * d_max);
+  w.C0 = c.take<float>(n_in * (size_t)m->dims[0]);
   w.kept_ids = c.take<int32_t>(B + 1);
   w.remap = c.take<int32_t>(B + 1);
   w.counters = c.take<int32_t>(64);
@@ -200,8 +203,15 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
   }
   {
     PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
+    SpmmRowPart part;
+    if (layer == 1 && ctx->cache_X != nullptr && ctx->cache_X == H_in) {
+      // inner neighbours are the same every epoch: their sum is cached, only the kept boundary
+      // tail of each row is aggregated now
+      part.row_skip = ctx->ws.split.n_inner;
+      part.init = ctx->ws.C0;
+    }
     BNS_TRY("spmm_fwd", spmm_fwd(ctx->ws.plan_f, n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx,
-                                 ctx->ws.dis_in, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, s));
+                                 ctx->ws.dis_in, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part, s));
   }
   {
     PhaseTimer t(ctx, BNS_PHASE_GEMM_FWD, s);
@@ -221,10 +231,23 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
     PhaseTimer t(ctx, BNS_PHASE_GEMM_DW, s);
     BNS_TRY("gemm_tn_splitk", gemm_tn_splitk(d_in, d_out, n_in, A_saved, dZ, dW, ctx->ws.partials, s));
   }
-  if (dH_in) {
+  if (dH_in && d_out < d_in) {
+    // (P^T dZ) W^T instead of P^T (dZ W^T): the transposed aggregate runs at the narrower width
+    float *G_in = ctx->ws.G1, *G_halo = dhalo ? ctx->ws.Hu : nullptr;
+    {
+      PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
+      BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_out, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
+                                   ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_halo,
+                                   halo_scale(p), dZ, nullptr, ctx->ws.spmm_partials, G_in, G_halo, s));
+    }
+    PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
+    BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, G_in, W, dH_in, mask_src, nullptr, s));
+    if (G_halo && B > 0)
+      BNS_TRY("gemm_nt(halo)", gemm_nt(B, d_in, d_out, G_halo, W, dhalo, nullptr, ctx->cur_n_kept, s));
+  } else if (dH_in) {
     {
       PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
-      BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, s));
+      BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, nullptr, nullptr, s));
     }
     PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
     BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_in, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
@@ -252,7 +275,7 @@ bns_status build_impl(bns_ctx *ctx, int32_t *row_ptr, int32_t *col_idx, int32_t 
   const bns_partition_desc &P = ctx->part;
   PhaseTimer t(ctx, BNS_PHASE_BUILD, s);
   BNS_TRY("build_sampled_csr",
-          build_sampled_csr(P.n_in, P.e_in, P.e_bd, ctx->ws.split, ctx->cur_remap, ctx->ws.kpos,
+          build_sampled_csr(P.n_in, P.e_in, P.e_bd, ctx->ws.split, ctx->ws.ballots, ctx->cur_remap, ctx->ws.kpos,
                             ctx->ws.tile_sums, row_ptr, col_idx, nnz, s));
   BNS_TRY("build_transposed_csr",
           build_transposed_csr(P.n_in, P.n_halo, P.e_in, P.t_in_ptr, P.t_in_col, P.halo_ptr, P.halo_col,
@@ -411,6 +434,22 @@ bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
     for (int l = 0; l < L; ++l)
       BNS_TRY("sgd_update", sgd_update((int64_t)ctx->dims[l] * ctx->dims[l + 1], W[l], dW[l], lr, s));
   }
+  return BNS_OK;
+}
+
+bns_status bns_cache_input_aggregate(bns_ctx *ctx, const float *X, void *stream) {
+  if (!ctx) return BNS_EINVAL;
+  ctx->cache_X = nullptr;
+  if (!X) return BNS_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // C0[v,:] = sum over the inner neighbours u of v of d~_u^-1/2 X[u,:]  (static CSR, inner entries only)
+  SpmmRowPart part;
+  part.row_take = ctx->ws.split.n_inner;
+  part.unscaled = true;
+  BNS_TRY("spmm_fwd(cache)", spmm_fwd(ctx->ws.plan_f, ctx->part.n_in, ctx->dims[0], ctx->part.row_ptr0,
+                                      ctx->part.col0, ctx->ws.dis_in, X, nullptr, ctx->ws.spmm_partials,
+                                      ctx->ws.C0, part, s));
+  ctx->cache_X = X;
   return BNS_OK;
 }
 

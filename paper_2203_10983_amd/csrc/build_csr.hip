@@ -86,14 +86,20 @@ hipError_t build_static_split(int32_t n_in, const int32_t *row_ptr0, const int32
 }
 
 // ---------------------------------------------------------------------------------- per epoch
+// The keep decision of a boundary node is one bit of the sampler's ballot words (a table of
+// n_halo/8 bytes that stays in L2); the 4-byte rank is only fetched for kept entries.
+__device__ __forceinline__ bool kept_bit(const uint64_t *__restrict__ ballots, int b) {
+  return (ballots[b >> 6] >> (b & 63)) & 1ull;
+}
+
 __global__ void __launch_bounds__(kThreads)
 bd_keep_tile_sums_kernel(int64_t e_bd, const int32_t *__restrict__ bd_b,
-                         const int32_t *__restrict__ remap, int32_t *__restrict__ tile_sums) {
+                         const uint64_t *__restrict__ ballots, int32_t *__restrict__ tile_sums) {
   const int64_t k0 = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kItems;
   int cnt = 0;
 #pragma unroll
   for (int i = 0; i < kItems; ++i)
-    if (k0 + i < e_bd) cnt += remap[bd_b[k0 + i]] >= 0;
+    if (k0 + i < e_bd) cnt += kept_bit(ballots, bd_b[k0 + i]);
   int total;
   block_exclusive_scan<kThreads>(cnt, &total);
   if (threadIdx.x == 0) tile_sums[blockIdx.x] = total;
@@ -101,15 +107,19 @@ bd_keep_tile_sums_kernel(int64_t e_bd, const int32_t *__restrict__ bd_b,
 
 __global__ void __launch_bounds__(kThreads)
 bd_fill_kernel(int32_t n_in, int64_t e_bd, const int32_t *__restrict__ bd_b,
-               const int32_t *__restrict__ bd_row, const int32_t *__restrict__ remap,
-               const int32_t *__restrict__ tile_offsets, const int32_t *__restrict__ inner_ptr,
+               const int32_t *__restrict__ bd_row, const uint64_t *__restrict__ ballots,
+               const int32_t *__restrict__ remap, const int32_t *__restrict__ tile_offsets, const int32_t *__restrict__ inner_ptr,
                int32_t *__restrict__ kpos, int32_t *__restrict__ col_idx) {
   const int64_t k0 = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kItems;
   int rank[kItems];
   int cnt = 0;
 #pragma unroll
   for (int i = 0; i < kItems; ++i) {
-    rank[i] = (k0 + i < e_bd) ? remap[bd_b[k0 + i]] : -1;
+    rank[i] = -1;
+    if (k0 + i < e_bd) {
+      const int b = bd_b[k0 + i];
+      if (kept_bit(ballots, b)) rank[i] = remap[b];
+    }
     cnt += rank[i] >= 0;
   }
   int total;
@@ -151,13 +161,13 @@ inner_fill_kernel(int64_t e_in, const int32_t *__restrict__ in_col,
 }
 
 hipError_t build_sampled_csr(int32_t n_in, int64_t e_in, int64_t e_bd, const StaticSplit &sp,
-                             const int32_t *remap, int32_t *kpos, int32_t *tile_sums,
+                             const uint64_t *ballots, const int32_t *remap, int32_t *kpos, int32_t *tile_sums,
                              int32_t *row_ptr, int32_t *col_idx, int32_t *nnz, hipStream_t s) {
   if (e_bd > 0) {
     const int nb = scan_tiles(e_bd);
-    bd_keep_tile_sums_kernel<<<nb, kThreads, 0, s>>>(e_bd, sp.bd_b, remap, tile_sums);
+    bd_keep_tile_sums_kernel<<<nb, kThreads, 0, s>>>(e_bd, sp.bd_b, ballots, tile_sums);
     (void)scan_sums_inplace(tile_sums, nb, nullptr, s);
-    bd_fill_kernel<<<nb, kThreads, 0, s>>>(n_in, e_bd, sp.bd_b, sp.bd_row, remap, tile_sums,
+    bd_fill_kernel<<<nb, kThreads, 0, s>>>(n_in, e_bd, sp.bd_b, sp.bd_row, ballots, remap, tile_sums,
                                            sp.inner_ptr, kpos, col_idx);
   }
   row_ptr_kernel<<<(n_in + 1 + kThreads - 1) / kThreads, kThreads, 0, s>>>(

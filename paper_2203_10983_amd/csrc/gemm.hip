@@ -4,11 +4,15 @@
 //   forward   H = A W            gemm_nn : A [M,K] k-contiguous,  B [K,N] n-contiguous
 //   backward  dA = dZ W^T        gemm_nt : A [M,K] k-contiguous,  B [N,K] k-contiguous
 //   backward  dW = A^T dZ        gemm_tn : A [K,M] m-contiguous,  B [K,N] n-contiguous, split K
-// A 256-thread block (4 wavefronts, 2x2) owns a 128x128 tile of C; each wavefront owns 64x64 as
-// 2x2 MFMA tiles of 32x32.  Operand tiles of depth 16 are staged through LDS in k-major order
-// (As[k][m], Bs[k][n]) so that an MFMA operand read is one conflict-free row segment; the next
-// tile is prefetched into registers while the current one is multiplied (double-buffered LDS,
-// one barrier per step).  Split-K partial tiles are summed in a fixed order: no atomics.
+// A 256-thread block (4 wavefronts) owns a 128 x BN tile of C.  BN = 128: wavefronts 2x2, each
+// 64x64 as 2x2 MFMA tiles of 32x32.  BN = 64 (chosen when it wastes fewer padded columns, e.g.
+// N = 172, 47, 41): wavefronts 4x1, each 32x64.  Operand tiles of depth 16 are staged through LDS
+// in k-major order (As[k][m], Bs[k][n]) so that an MFMA operand read is one conflict-free row
+// segment; the next tile is prefetched into registers while the current one is multiplied
+// (double-buffered LDS, one barrier per step).  Split-K partial tiles are summed in a fixed
+// order: no atomics.
+#include <type_traits>
+
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -16,14 +20,13 @@ namespace bns {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 16;
-constexpr int LDS_LD = BM + 4;  // row stride of a staged tile in floats (keeps 16-byte alignment)
+constexpr int BM = 128, BK = 16;
 constexpr int kGemmThreads = 256;
 
-// Tile of an operand stored [rows][K] (k-contiguous): 128 rows x 16 k, as 2 x float4 per thread.
-struct FragK { float4 v[2]; };
-// Tile of an operand stored [K][cols] (contiguous along the tile's 128 columns).
-struct FragN { float4 v[2]; };
+// Tile of an operand stored [rows][K] (k-contiguous): ROWS rows x 16 k, one float4 per thread and pass.
+template <int ROWS> struct FragK { float4 v[ROWS / 64]; };
+// Tile of an operand stored [K][cols] (contiguous along the tile's COLS columns).
+template <int COLS> struct FragN { float4 v[COLS / 64]; };
 
 __device__ __forceinline__ float4 load4_guarded(const float *p, bool vec_ok, int valid) {
   // valid = number of leading elements (0..4) that are in range
@@ -38,92 +41,111 @@ __device__ __forceinline__ float4 load4_guarded(const float *p, bool vec_ok, int
 
 __device__ __forceinline__ int clamp04(int x) { return x < 0 ? 0 : (x > 4 ? 4 : x); }
 
-// rows: row0.. of an operand [R][ld] (k-contiguous); k range [k0, k0+16) limited by k_end
-__device__ __forceinline__ void load_kcontig(FragK &f, const float *__restrict__ base, int ld,
+// rows row0.. of an operand [R][ld] (k-contiguous); k range [k0, k0+16) limited by k_end
+template <int ROWS>
+__device__ __forceinline__ void load_kcontig(FragK<ROWS> &f, const float *__restrict__ base, int ld,
                                              int row0, int n_rows, int k0, int k_end, bool vec_ok) {
   const int t = threadIdx.x;
   const int kq = (t & 3) * 4;
 #pragma unroll
-  for (int p = 0; p < 2; ++p) {
+  for (int p = 0; p < ROWS / 64; ++p) {
     const int r = row0 + (t >> 2) + p * 64;
     const int valid = r < n_rows ? clamp04(k_end - (k0 + kq)) : 0;
     f.v[p] = load4_guarded(base + (size_t)r * ld + k0 + kq, vec_ok, valid);
   }
 }
-__device__ __forceinline__ void store_kcontig(const FragK &f, float *__restrict__ tile) {
+template <int ROWS>
+__device__ __forceinline__ void store_kcontig(const FragK<ROWS> &f, float *__restrict__ tile) {
+  constexpr int LD = ROWS + 4;
   const int t = threadIdx.x;
   const int kq = (t & 3) * 4;
 #pragma unroll
-  for (int p = 0; p < 2; ++p) {
+  for (int p = 0; p < ROWS / 64; ++p) {
     const int r = (t >> 2) + p * 64;
-    tile[(kq + 0) * LDS_LD + r] = f.v[p].x;
-    tile[(kq + 1) * LDS_LD + r] = f.v[p].y;
-    tile[(kq + 2) * LDS_LD + r] = f.v[p].z;
-    tile[(kq + 3) * LDS_LD + r] = f.v[p].w;
+    tile[(kq + 0) * LD + r] = f.v[p].x;
+    tile[(kq + 1) * LD + r] = f.v[p].y;
+    tile[(kq + 2) * LD + r] = f.v[p].z;
+    tile[(kq + 3) * LD + r] = f.v[p].w;
   }
 }
 
-// operand [K][ld] with the tile's 128 columns starting at col0
-__device__ __forceinline__ void load_ncontig(FragN &f, const float *__restrict__ base, int ld,
+// operand [K][ld] with the tile's COLS columns starting at col0
+template <int COLS>
+__device__ __forceinline__ void load_ncontig(FragN<COLS> &f, const float *__restrict__ base, int ld,
                                              int col0, int n_cols, int k0, int k_end, bool vec_ok) {
+  constexpr int TPR = COLS / 4;              // threads per k-row
+  constexpr int KPP = kGemmThreads / TPR;    // k-rows per pass
   const int t = threadIdx.x;
-  const int cq = (t & 31) * 4;
+  const int cq = (t % TPR) * 4;
 #pragma unroll
-  for (int p = 0; p < 2; ++p) {
-    const int k = k0 + (t >> 5) + p * 8;
+  for (int p = 0; p < BK / KPP; ++p) {
+    const int k = k0 + t / TPR + p * KPP;
     const int valid = k < k_end ? clamp04(n_cols - (col0 + cq)) : 0;
     f.v[p] = load4_guarded(base + (size_t)k * ld + col0 + cq, vec_ok, valid);
   }
 }
-__device__ __forceinline__ void store_ncontig(const FragN &f, float *__restrict__ tile) {
+template <int COLS>
+__device__ __forceinline__ void store_ncontig(const FragN<COLS> &f, float *__restrict__ tile) {
+  constexpr int LD = COLS + 4;
+  constexpr int TPR = COLS / 4;
+  constexpr int KPP = kGemmThreads / TPR;
   const int t = threadIdx.x;
-  const int cq = (t & 31) * 4;
+  const int cq = (t % TPR) * 4;
 #pragma unroll
-  for (int p = 0; p < 2; ++p) {
-    const int k = (t >> 5) + p * 8;
-    *reinterpret_cast<float4 *>(&tile[k * LDS_LD + cq]) = f.v[p];
+  for (int p = 0; p < BK / KPP; ++p) {
+    const int k = t / TPR + p * KPP;
+    *reinterpret_cast<float4 *>(&tile[k * LD + cq]) = f.v[p];
   }
 }
 
-template <bool A_KCONTIG, bool B_KCONTIG, bool RELU>
+// EPI: 0 = store, 1 = ReLU, 2 = zero where mask_src <= 0 (ReLU mask of the backward pass).
+// m_dev (nullable): the row count lives on the device (*m_dev <= M); tiles past it do nothing.
+template <int BN, bool A_KCONTIG, bool B_KCONTIG, int EPI>
 __global__ void __launch_bounds__(kGemmThreads)
 gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const float *__restrict__ B,
-            int ldb, float *__restrict__ C, int ldc, int k_chunk, bool vec_a, bool vec_b) {
-  __shared__ __attribute__((aligned(16))) float As[2][BK * LDS_LD];
-  __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDS_LD];
+            int ldb, float *__restrict__ C, int ldc, int k_chunk, bool vec_a, bool vec_b,
+            const float *__restrict__ mask_src, const int *__restrict__ m_dev) {
+  constexpr int LDA = BM + 4, LDB = BN + 4;  // row strides of the staged tiles (16-byte aligned rows)
+  constexpr int TI = BN == 128 ? 2 : 1;      // 32-row MFMA tiles per wavefront
+  const int m_full = M;
+  if (m_dev) M = min(M, *m_dev);
+  __shared__ __attribute__((aligned(16))) float As[2][BK * LDA];
+  __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDB];
 
   const int tiles_n = (N + BN - 1) / BN;
   const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
   const int bm0 = tm * BM, bn0 = tn * BN;
+  if (bm0 >= M) return;
   const int k_begin = blockIdx.y * k_chunk;
   const int k_end = min(K, k_begin + k_chunk);
-  C += (size_t)blockIdx.y * M * ldc;  // split-K: one partial matrix per split
+  C += (size_t)blockIdx.y * m_full * ldc;  // split-K: one partial matrix per split
 
   const int lane = lane_id(), wid = threadIdx.x >> 6;
-  const int wm = (wid >> 1) * 64, wn = (wid & 1) * 64;
+  const int wm = BN == 128 ? (wid >> 1) * 64 : wid * 32;
+  const int wn = BN == 128 ? (wid & 1) * 64 : 0;
   const int l32 = lane & 31, lhi = lane >> 5;
 
-  floatx16 acc[2][2];
+  floatx16 acc[TI][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  using FA = typename std::conditional<A_KCONTIG, FragK, FragN>::type;
-  using FB = typename std::conditional<B_KCONTIG, FragK, FragN>::type;
+  using FA = typename std::conditional<A_KCONTIG, FragK<BM>, FragN<BM>>::type;
+  using FB = typename std::conditional<B_KCONTIG, FragK<BN>, FragN<BN>>::type;
   FA fa;
   FB fb;
   auto load_tiles = [&](int k0) {
-    if constexpr (A_KCONTIG) load_kcontig(fa, A, lda, bm0, M, k0, k_end, vec_a);
-    else load_ncontig(fa, A, lda, bm0, M, k0, k_end, vec_a);
-    if constexpr (B_KCONTIG) load_kcontig(fb, B, ldb, bn0, N, k0, k_end, vec_b);
-    else load_ncontig(fb, B, ldb, bn0, N, k0, k_end, vec_b);
+    if constexpr (A_KCONTIG) load_kcontig<BM>(fa, A, lda, bm0, M, k0, k_end, vec_a);
+    else load_ncontig<BM>(fa, A, lda, bm0, M, k0, k_end, vec_a);
+    if constexpr (B_KCONTIG) load_kcontig<BN>(fb, B, ldb, bn0, N, k0, k_end, vec_b);
+    else load_ncontig<BN>(fb, B, ldb, bn0, N, k0, k_end, vec_b);
   };
   auto store_tiles = [&](int buf) {
-    if constexpr (A_KCONTIG) store_kcontig(fa, As[buf]); else store_ncontig(fa, As[buf]);
-    if constexpr (B_KCONTIG) store_kcontig(fb, Bs[buf]); else store_ncontig(fb, Bs[buf]);
+    if constexpr (A_KCONTIG) store_kcontig<BM>(fa, As[buf]); else store_ncontig<BM>(fa, As[buf]);
+    if constexpr (B_KCONTIG) store_kcontig<BN>(fb, Bs[buf]); else store_ncontig<BN>(fb, Bs[buf]);
   };
 
   const int nk = (k_end - k_begin + BK - 1) / BK;
@@ -139,13 +161,15 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
     const float *bs = Bs[buf] + wn + l32;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
-      const int krow = (kk + lhi) * LDS_LD;
-      const float a0 = as[krow], a1 = as[krow + 32];
-      const float b0 = bs[krow], b1 = bs[krow + 32];
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+      float a[TI];
+#pragma unroll
+      for (int i = 0; i < TI; ++i) a[i] = as[(kk + lhi) * LDA + i * 32];
+      const float b0 = bs[(kk + lhi) * LDB], b1 = bs[(kk + lhi) * LDB + 32];
+#pragma unroll
+      for (int i = 0; i < TI; ++i) {
+        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b0, acc[i][0], 0, 0, 0);
+        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b1, acc[i][1], 0, 0, 0);
+      }
     }
     if (kt + 1 < nk) store_tiles(buf ^ 1);
     __syncthreads();
@@ -153,7 +177,7 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
 
   // C tile element held by (lane, register r): row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int col = bn0 + wn + j * 32 + l32;
@@ -163,7 +187,8 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
         const int row = bm0 + wm + i * 32 + (r >> 2) * 8 + lhi * 4 + (r & 3);
         if (row < M) {
           float x = acc[i][j][r];
-          if (RELU) x = fmaxf(x, 0.f);
+          if (EPI == 1) x = fmaxf(x, 0.f);
+          if (EPI == 2) x = mask_src[(size_t)row * ldc + col] > 0.f ? x : 0.f;
           C[(size_t)row * ldc + col] = x;
         }
       }
@@ -172,24 +197,42 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
 
 static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 
+// Column-tile width: the one that pads N to fewer columns (ties go to the wider tile).
+static inline int pick_bn(int N) {
+  const int pad128 = (N + 127) / 128 * 128, pad64 = (N + 63) / 64 * 64;
+  return pad64 < pad128 ? 64 : 128;
+}
+static inline unsigned n_tiles(int M, int N, int bn) {
+  return (unsigned)(((M + BM - 1) / BM) * ((N + bn - 1) / bn));
+}
+
+#define BNS_GEMM_LAUNCH(AK, BK_, EPI, grid, ...)                                                 \
+  do {                                                                                           \
+    if (bn == 64) gemm_kernel<64, AK, BK_, EPI><<<grid, kGemmThreads, 0, s>>>(__VA_ARGS__);      \
+    else gemm_kernel<128, AK, BK_, EPI><<<grid, kGemmThreads, 0, s>>>(__VA_ARGS__);              \
+  } while (0)
+
 hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
                    bool relu, hipStream_t s) {
-  const unsigned tiles = (unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN));
+  const int bn = pick_bn(N);
+  const unsigned tiles = n_tiles(M, N, bn);
   if (tiles == 0) return hipSuccess;
   const bool va = (K % 4 == 0) && aligned16(A), vb = (N % 4 == 0) && aligned16(B);
-  if (relu)
-    gemm_kernel<true, false, true><<<dim3(tiles, 1), kGemmThreads, 0, s>>>(M, N, K, A, K, B, N, C, N, K, va, vb);
-  else
-    gemm_kernel<true, false, false><<<dim3(tiles, 1), kGemmThreads, 0, s>>>(M, N, K, A, K, B, N, C, N, K, va, vb);
+  const dim3 grid(tiles, 1);
+  if (relu) BNS_GEMM_LAUNCH(true, false, 1, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, nullptr);
+  else BNS_GEMM_LAUNCH(true, false, 0, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, nullptr);
   return hipGetLastError();
 }
 
 hipError_t gemm_nt(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   hipStream_t s) {
-  const unsigned tiles = (unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN));
+                   const float *mask_src, const int32_t *m_dev, hipStream_t s) {
+  const int bn = pick_bn(N);
+  const unsigned tiles = n_tiles(M, N, bn);
   if (tiles == 0) return hipSuccess;
   const bool va = (K % 4 == 0) && aligned16(A), vb = (K % 4 == 0) && aligned16(B);
-  gemm_kernel<true, true, false><<<dim3(tiles, 1), kGemmThreads, 0, s>>>(M, N, K, A, K, B, K, C, N, K, va, vb);
+  const dim3 grid(tiles, 1);
+  if (mask_src) BNS_GEMM_LAUNCH(true, true, 2, grid, M, N, K, A, K, B, K, C, N, K, va, vb, mask_src, m_dev);
+  else BNS_GEMM_LAUNCH(true, true, 0, grid, M, N, K, A, K, B, K, C, N, K, va, vb, nullptr, m_dev);
   return hipGetLastError();
 }
 
@@ -198,7 +241,7 @@ constexpr int kSplitTargetBlocks = 768;
 constexpr int kReduceGroup = 16;
 
 static inline int splitk_chunk(int32_t M, int32_t N, int32_t K, int *splits_out) {
-  const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  const int tiles = (int)n_tiles(M, N, pick_bn(N));
   int splits = (kSplitTargetBlocks + tiles - 1) / tiles;
   const int max_splits = (K + 4 * BK - 1) / (4 * BK);  // at least 64 rows of K per split
   if (splits > max_splits) splits = max_splits;
@@ -232,15 +275,16 @@ splitk_reduce_kernel(const float *__restrict__ in, float *__restrict__ out, int6
 
 hipError_t gemm_tn_splitk(int32_t M, int32_t N, int32_t K, const float *A, const float *B,
                           float *C, float *partials, hipStream_t s) {
-  const unsigned tiles = (unsigned)(((M + BM - 1) / BM) * ((N + BN - 1) / BN));
+  const int bn = pick_bn(N);
+  const unsigned tiles = n_tiles(M, N, bn);
   if (tiles == 0) return hipSuccess;
   int splits;
   const int chunk = splitk_chunk(M, N, K, &splits);
   const bool va = (M % 4 == 0) && aligned16(A), vb = (N % 4 == 0) && aligned16(B);
   const int64_t mn = (int64_t)M * N;
   float *dst = splits == 1 ? C : partials;
-  gemm_kernel<false, false, false><<<dim3(tiles, splits), kGemmThreads, 0, s>>>(
-      M, N, K, A, M, B, N, dst, N, chunk, va, vb);
+  const dim3 grid(tiles, splits);
+  BNS_GEMM_LAUNCH(false, false, 0, grid, M, N, K, A, M, B, N, dst, N, chunk, va, vb, nullptr, nullptr);
   // grouped, fixed-order reduction: partials -> level 2 -> ... -> C
   float *cur = partials;
   float *nxt = partials + (size_t)splits * mn;

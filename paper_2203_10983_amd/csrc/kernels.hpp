@@ -41,9 +41,10 @@ hipError_t build_static_split(int32_t n_in, const int32_t *row_ptr0, const int32
                               const StaticSplit &sp, int32_t *tile_sums, hipStream_t s);
 hipError_t degree_rsqrt(const int32_t *deg, int32_t n, float *dis, hipStream_t s);
 
-// kpos: scratch int32[e_bd+1]; tile_sums: scratch int32[scan_tiles(e_bd)+1].
+// ballots: the keep bits written by sample_boundary (bit b%64 of word b/64); kpos: scratch
+// int32[e_bd+1]; tile_sums: scratch int32[scan_tiles(e_bd)+1].
 hipError_t build_sampled_csr(int32_t n_in, int64_t e_in, int64_t e_bd, const StaticSplit &sp,
-                             const int32_t *remap, int32_t *kpos, int32_t *tile_sums,
+                             const uint64_t *ballots, const int32_t *remap, int32_t *kpos, int32_t *tile_sums,
                              int32_t *row_ptr, int32_t *col_idx, int32_t *nnz, hipStream_t s);
 // hlen: scratch int32[n_halo]; tile_sums: scratch int32[scan_tiles(n_halo)+1].
 hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
@@ -79,9 +80,17 @@ hipError_t halo_gather(const float *halo_h, const int32_t *kept_ids, const int32
                        hipStream_t s);
 // A[v,:] = dis_in[v] * ( sum_{u<n_in in row v} dis_in[u] H_in[u,:] + sum_{kept r in row v} Hu[r,:] )
 // plan: segmentation of the static local CSR; partials: scratch f32[plan.n_part * d].
+// part (all optional) restricts every row to entries [skip, skip+take) of its list, adds an
+// initial row vector before scaling, or leaves out the dis_in[v] row factor.
+struct SpmmRowPart {
+  const int32_t *row_skip = nullptr;
+  const int32_t *row_take = nullptr;
+  const float *init = nullptr;
+  bool unscaled = false;
+};
 hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
                     const int32_t *col_idx, const float *dis_in, const float *H_in, const float *Hu,
-                    float *partials, float *A, hipStream_t s);
+                    float *partials, float *A, const SpmmRowPart &part, hipStream_t s);
 // For stacked column u < n_in + *n_kept:  g = sum_{v in t_row u} dis_in[v] dA[v,:];
 //   u <  n_in: dH_in[u,:] = dis_in[u] * g   (zeroed where mask_src[u,:] <= 0 if mask_src != null)
 //   u >= n_in: dhalo[u-n_in,:] = s_halo * dis_halo[kept_ids[u-n_in]] * g   (skipped if dhalo null)
@@ -96,9 +105,10 @@ hipError_t spmm_bwd(const SegPlan &plan, int32_t n_in, int32_t n_halo, int32_t d
 // C[M,N] = A[M,K] B[K,N], optional ReLU.
 hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
                    bool relu, hipStream_t s);
-// C[M,N] = A[M,K] B[N,K]^T.
+// C[M,N] = A[M,K] B[N,K]^T.  mask_src (nullable, [M,N]): C is zeroed where mask_src <= 0.
+// m_dev (nullable): device-side row count, *m_dev <= M; rows past it are not touched.
 hipError_t gemm_nt(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   hipStream_t s);
+                   const float *mask_src, const int32_t *m_dev, hipStream_t s);
 // C[M,N] = A[K,M]^T B[K,N] with K split over the grid; partials: scratch f32[splits*M*N],
 // summed in a fixed order.  splitk_splits() gives the split count used for (M,N,K).
 int32_t splitk_splits(int32_t M, int32_t N, int32_t K);

@@ -13,17 +13,18 @@
 // sums at the end.  Column indices and their weights are fetched 64 at a time, one per lane,
 // and handed to the loop by cross-lane reads, four neighbours in flight per step.
 #include <algorithm>
-#include <cstdlib>
 
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
 namespace bns {
 
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 template <int VEC> struct Vec;
 template <> struct Vec<1> { using T = float; };
-template <> struct Vec<2> { using T = float2; };
-template <> struct Vec<4> { using T = float4; };
+template <> struct Vec<2> { using T = v2f; };
+template <> struct Vec<4> { using T = v4f; };
 
 template <int VEC>
 __device__ __forceinline__ void vec_fma(float (&acc)[VEC], float w, const typename Vec<VEC>::T &v) {
@@ -47,6 +48,10 @@ struct SpmmArgs {
   const int32_t *kept_ids;     // out1 row r is scaled by s_halo * dis_halo[kept_ids[r]]
   const float *dis_halo;
   float s_halo;
+  // optional restriction of rows < n_split to a part of their entries, and an initial value:
+  const int32_t *row_skip;     // skip the first row_skip[row] entries (nullable)
+  const int32_t *row_take;     // then use row_take[row] entries instead of the rest (nullable)
+  const float *init;           // out0 row = scale * (init row + sum) (nullable)
 };
 
 // Scale, optional ReLU mask and store of one finished row slice held as acc[c][i].
@@ -58,8 +63,10 @@ __device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, i
   float scale;
   float *out;
   const float *mask = nullptr;
+  const float *init = nullptr;
   if (row < a.n_split) {
-    scale = a.out_scale0[row];
+    if (a.init) init = a.init + (size_t)row * d;
+    scale = a.out_scale0 ? a.out_scale0[row] : 1.f;
     out = a.out0 + (size_t)row * d;
     if (a.mask_src) mask = a.mask_src + (size_t)row * d;
   } else {
@@ -75,7 +82,15 @@ __device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, i
       V o;
       float *po = reinterpret_cast<float *>(&o);
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) po[i] = acc[c][i] * scale;
+      for (int i = 0; i < VEC; ++i) po[i] = acc[c][i];
+      if (init) {
+        const V x0 = reinterpret_cast<const V *>(init)[iv];
+        const float *p0 = reinterpret_cast<const float *>(&x0);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) po[i] += p0[i];
+      }
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) po[i] *= scale;
       if (mask) {
         const V m = reinterpret_cast<const V *>(mask)[iv];
         const float *pm = reinterpret_cast<const float *>(&m);
@@ -109,6 +124,10 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
     row = a.n_split + (unit - a.plan.n_seg);
   }
   int e0 = a.row_ptr[row], e1 = a.row_ptr[row + 1];
+  if (row < a.n_split) {
+    if (a.row_skip) e0 += a.row_skip[row];
+    if (a.row_take) e1 = e0 + a.row_take[row];
+  }
   if (nseg > 1) {  // this wavefront's slice of the row as it is in this epoch
     const int chunk = (e1 - e0 + nseg - 1) / nseg;
     e0 = min(e1, e0 + seg * chunk);
@@ -280,13 +299,14 @@ static hipError_t launch_spmm(const SpmmArgs &a, int64_t max_units, hipStream_t 
 
 hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
                     const int32_t *col_idx, const float *dis_in, const float *H_in, const float *Hu,
-                    float *partials, float *A, hipStream_t s) {
+                    float *partials, float *A, const SpmmRowPart &part, hipStream_t s) {
   SpmmArgs a{};
   a.plan = plan; a.n_extra_dev = nullptr; a.d = d;
   a.row_ptr = row_ptr; a.col_idx = col_idx; a.n_split = n_in;
   a.src0 = H_in; a.src1 = Hu; a.w_col = dis_in; a.partials = partials;
-  a.out0 = A; a.out1 = nullptr; a.out_scale0 = dis_in; a.mask_src = nullptr;
+  a.out0 = A; a.out1 = nullptr; a.out_scale0 = part.unscaled ? nullptr : dis_in; a.mask_src = nullptr;
   a.kept_ids = nullptr; a.dis_halo = nullptr; a.s_halo = 0.f;
+  a.row_skip = part.row_skip; a.row_take = part.row_take; a.init = part.init;
   return launch_spmm(a, plan.n_seg, s);
 }
 

@@ -235,3 +235,37 @@ def test_train_step_end_to_end(case):
             assert np.abs(g_gpu - g_ref).max() <= 2e-2 * np.abs(g_ref).max(), f"dW[{l}] (with ties)"
     for l in range(1, L):
         assert np.all(dhalo[l][n_u:].cpu().numpy() == 0.0)
+
+
+def test_train_step_with_cached_input_aggregate(case):
+    """Static-inner caching (bns_cache_input_aggregate): layer 1 aggregates only the kept boundary
+    tail of each row on top of the cached inner sum; results must still match the oracle."""
+    c, p, epoch = case
+    w, P, torch, pkg = c.w, c.w.part, c.torch, c.pkg
+    _log(f"[test] cached input aggregate cfg={w.cfg} {w.name} p={p} epoch={epoch}")
+    ref = c.oracle(p, epoch)
+    L = w.n_layers
+    f32 = dict(dtype=torch.float32, device=c.dev)
+    dW = [torch.empty_like(x) for x in c.W]
+    loss = torch.zeros(1, **f32)
+    c.ctx.cache_input_aggregate(c.X)
+    try:
+        c.ctx.train_step(SAMPLING_SEED, epoch, p, c.X, c.halo_h, c.labels, c.W, dW, None, loss, 0.0)
+        torch.cuda.synchronize()
+        for l in range(1, L + 1):
+            A = c.ctx.ws_tensor(pkg.VIEW_A, l, torch.float32).cpu().numpy().reshape(P.n_in, w.dims[l - 1])
+            H = c.ctx.ws_tensor(pkg.VIEW_H, l, torch.float32).cpu().numpy().reshape(P.n_in, w.dims[l])
+            assert_close(A, ref["A"][l], f"A[{l}] (cached)")
+            assert_close(H, ref["H"][l], f"H[{l}] (cached)")
+        assert abs(float(loss[0]) - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+        # the last layer's weight gradient does not pass through any ReLU decision
+        assert_close(dW[L - 1].cpu().numpy(), ref["dW"][L - 1], f"dW[{L}] (cached)")
+        # a different input pointer must not use the cache
+        X2 = c.X.clone()
+        A1 = torch.empty(P.n_in, w.dims[0], **f32)
+        H1 = torch.empty(P.n_in, w.dims[1], **f32)
+        c.ctx.gcn_layer_fwd(1, p, X2, c.halo_h[0], c.W[0], A1, H1, L > 1)
+        torch.cuda.synchronize()
+        assert_close(A1.cpu().numpy(), ref["A"][1], "A[1] (other pointer, uncached)")
+    finally:
+        c.ctx.cache_input_aggregate(None)
