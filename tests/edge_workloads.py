@@ -1,0 +1,71 @@
+"""Small hand-shaped workloads for the degenerate cases of the partition step."""
+import numpy as np
+
+from bns_inputs import Workload
+from bns_inputs.partition import partition_from_entries
+from bns_inputs.workloads import glorot_weights
+
+
+def _finish(name, part, dims, loss_kind, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    L = len(dims) - 1
+    X = rng.standard_normal((part.n_in, dims[0]), dtype=np.float32)
+    halo_h = [rng.standard_normal((part.n_halo, dims[l]), dtype=np.float32) for l in range(L)]
+    for h in halo_h[1:]:
+        np.maximum(h, 0.0, out=h)
+    if loss_kind == 0:
+        labels = rng.integers(0, dims[-1], size=part.n_in).astype(np.int32)
+    else:
+        labels = (rng.random((part.n_in, dims[-1])) < 0.3).astype(np.uint8)
+    return Workload(cfg=name, name=name, part=part, dims=list(dims), loss_kind=loss_kind, X=X,
+                    halo_h=halo_h, labels=labels, W=glorot_weights(seed + 1, list(dims)), p_list=[0.5])
+
+
+def no_boundary():
+    """A partition with an empty boundary set (|B| = 0): a circulant graph owned entirely."""
+    n = 300
+    src = np.repeat(np.arange(n), 4)
+    dst = (src + np.tile([-2, -1, 1, 2], n)) % n
+    part = partition_from_entries(3, n, src, dst, np.zeros(0, np.int64), np.zeros(0, np.int64))
+    return _finish("edge-no-boundary", part, [12, 8, 4], 0, 11)
+
+
+def star():
+    """One inner hub adjacent to every inner node (a row of 3000 entries: many segments) and one
+    boundary hub adjacent to every inner node (a transposed row far longer than a segment), plus
+    boundary leaves; odd feature widths (scalar-load path)."""
+    n = 3000
+    others = np.arange(1, n)
+    src_in = np.concatenate([np.zeros(n - 1, np.int64), others])
+    dst_in = np.concatenate([others, np.zeros(n - 1, np.int64)])
+    src_bd = np.concatenate([np.arange(n), np.arange(0, n, 7)])
+    dst_gid = np.concatenate([np.full(n, 10_000_000_000), 20_000_000_000 + np.arange(0, n, 7)])
+    part = partition_from_entries(1, n, src_in, dst_in, src_bd, dst_gid,
+                                  halo_full_degree=lambda g, inc: inc * 3)
+    return _finish("edge-star", part, [7, 5, 3], 0, 12)
+
+
+def single_node():
+    """|V| = 1 with two boundary neighbours; widths 1 and 2; multi-label loss."""
+    part = partition_from_entries(0, 1, np.zeros(0, np.int64), np.zeros(0, np.int64),
+                                  np.zeros(2, np.int64), np.array([5, 9], np.int64))
+    return _finish("edge-single-node", part, [1, 2, 2], 1, 13)
+
+
+def wide_odd():
+    """Widths that are multiples of 2 but not of 4 (two-float loads) and above one wavefront pass
+    (602 = 5 passes of 64 lanes), with a ragged number of rows."""
+    rng = np.random.Generator(np.random.PCG64(14))
+    n = 517
+    src = rng.integers(0, n, size=4000)
+    dst = rng.integers(0, n, size=4000)
+    keep = src != dst
+    src, dst = src[keep], dst[keep]
+    src_bd = rng.integers(0, n, size=900)
+    dst_gid = 1000 + rng.integers(0, 400, size=900)
+    part = partition_from_entries(2, n, np.concatenate([src, dst]), np.concatenate([dst, src]), src_bd, dst_gid,
+                                  halo_full_degree=lambda g, inc: inc + 5)
+    return _finish("edge-wide-odd", part, [602, 130, 66, 9], 0, 15)
+
+
+EDGE = {"e-nobd": no_boundary, "e-star": star, "e-single": single_node, "e-wide": wide_odd}

@@ -20,6 +20,7 @@ import pytest
 
 from bns_inputs import SAMPLING_SEED, make_workload
 from oracle import bns_oracle as orc
+from edge_workloads import EDGE
 from parity_util import assert_close, rel_err, strict_rel_err, tie_count
 
 pytestmark = pytest.mark.gpu
@@ -28,7 +29,10 @@ pytestmark = pytest.mark.gpu
 SMALL = [(1, 1, [0.1, 0.0, 1.0, 0.5], 0), (2, 16, [0.1, 1.0], 1), (3, 32, [0.1], 2),
          (4, 16, [0.1, 0.0], 3), (5, 64, [0.1, 0.01], 4)]
 FULL = [(2, 1, [1.0, 0.1, 0.01], 0), (3, 1, [0.1], 0), (4, 1, [0.1], 0), (5, 1, [0.1], 0)]
-CASES = [(c, s, p, e) for (c, s, ps, e) in SMALL + FULL for p in ps]
+# degenerate shapes (tests/edge_workloads.py): empty boundary, hub rows, one node, odd widths
+EDGES = [("e-nobd", 1, [0.5, 1.0], 0), ("e-star", 1, [0.5, 0.0, 1.0], 1), ("e-single", 1, [0.5, 0.0, 1.0], 2),
+         ("e-wide", 1, [0.5], 3)]
+CASES = [(c, s, p, e) for (c, s, ps, e) in EDGES + SMALL + FULL for p in ps]
 
 
 def _log(msg):
@@ -45,7 +49,7 @@ class _Case:
         import torch
         import paper_2203_10983_amd as pkg
         self.torch, self.pkg = torch, pkg
-        self.w = make_workload(cfg, scale=scale)
+        self.w = EDGE[cfg]() if isinstance(cfg, str) else make_workload(cfg, scale=scale)
         w = self.w
         dev = torch.device("cuda:0")
         self.dev = dev
@@ -82,7 +86,7 @@ class _Case:
         return self.torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev)
 
 
-@pytest.fixture(scope="module", params=CASES, ids=lambda c: f"cfg{c[0]}-s{c[1]}-p{c[2]}")
+@pytest.fixture(scope="module", params=CASES, ids=lambda c: f"cfg{c[0]}-s{c[1]}-p{c[2]}-")
 def case(request):
     cfg, scale, p, epoch = request.param
     return _Case.get(cfg, scale), p, epoch
