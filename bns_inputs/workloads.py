@@ -126,3 +126,14 @@ def make_workload(cfg: int, scale: int = 1, part_id: int = 0) -> Workload:
     return Workload(cfg=cfg, name=c["name"] + ("" if scale == 1 else f"/scale{scale}"),
                     part=part, dims=dims, loss_kind=c["loss"], X=X, halo_h=halo_h,
                     labels=labels, W=W, p_list=list(c["p_list"]))
+
+
+def sage_weights(seed: int, dims: List[int]) -> List[np.ndarray]:
+    """Weights of a GraphSAGE-mean model: per layer f32[2*d_in, d_out], the half that multiplies
+    the neighbour mean on top of the half that multiplies the node's own feature."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for fan_in, fan_out in zip(dims[:-1], dims[1:]):
+        lim = np.sqrt(6.0 / (2 * fan_in + fan_out))
+        out.append(rng.uniform(-lim, lim, size=(2 * fan_in, fan_out)).astype(np.float32))
+    return out

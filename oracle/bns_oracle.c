@@ -166,3 +166,60 @@ void bnso_aggregate_bwd(int64_t n_in, int64_t n_kept, int64_t d, const int32_t *
     for (int64_t j = 0; j < d; ++j) g[j] *= su;
   }
 }
+
+/* ------------------------------------------------------------------------- *
+ * GraphSAGE with a mean aggregator (Section 2: zeta = mean over the neighbours,
+ * phi = sigma(W . CONCAT(z_v, h_v))), the instance the paper trains.  Under
+ * boundary sampling the received boundary features are divided by p
+ * (Section 3.2, "for a mean aggregator we replace H with H/p"), and the mean
+ * keeps the FULL-graph neighbour count, so that the estimate is unbiased:
+ *   z_v = ( sum_{inner u ~ v} h_u + (1/p) sum_{kept boundary u ~ v} h_u ) / deg_v ,
+ * deg_v = number of neighbours of v in the whole graph (no self-loop).  The
+ * stored pattern carries one self-loop per row; the mean skips it.
+ * ------------------------------------------------------------------------- */
+void bnso_aggregate_mean(int64_t n_in, int64_t d, const int32_t *row_ptr, const int32_t *col_idx,
+                         const int32_t *deg_in, const int32_t *kept_ids, double s_halo,
+                         const double *H_in, const float *halo_h, double *Z) {
+#pragma omp parallel for schedule(dynamic, 64)
+  for (int64_t v = 0; v < n_in; ++v) {
+    double *z = Z + v * d;
+    for (int64_t j = 0; j < d; ++j) z[j] = 0.0;
+    for (int64_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+      const int64_t u = col_idx[e];
+      if (u == v) continue; /* the self-loop is not a neighbour */
+      if (u < n_in) {
+        const double *h = H_in + u * d;
+        for (int64_t j = 0; j < d; ++j) z[j] += h[j];
+      } else {
+        const float *h = halo_h + (int64_t)kept_ids[u - n_in] * d;
+        for (int64_t j = 0; j < d; ++j) z[j] += s_halo * (double)h[j];
+      }
+    }
+    const int64_t deg = (int64_t)deg_in[v] - 1; /* deg_in counts the self-loop */
+    const double inv = deg > 0 ? 1.0 / (double)deg : 0.0;
+    for (int64_t j = 0; j < d; ++j) z[j] *= inv;
+  }
+}
+
+/* Backward of the mean aggregate through the transposed pattern:
+ *   u inner:          dH_in[u,:]        = sum_{v ~ u, v != u} dZ[v,:] / deg_v
+ *   u kept boundary:  dhalo[u - n_in,:] = s_halo * sum_{v ~ u} dZ[v,:] / deg_v          */
+void bnso_aggregate_mean_bwd(int64_t n_in, int64_t n_kept, int64_t d, const int32_t *t_row_ptr,
+                             const int32_t *t_col_idx, const int32_t *deg_in, double s_halo,
+                             const double *dZ, double *dH_in, double *dhalo) {
+#pragma omp parallel for schedule(dynamic, 64)
+  for (int64_t u = 0; u < n_in + n_kept; ++u) {
+    double *g = u < n_in ? dH_in + u * d : dhalo + (u - n_in) * d;
+    for (int64_t j = 0; j < d; ++j) g[j] = 0.0;
+    for (int64_t e = t_row_ptr[u]; e < t_row_ptr[u + 1]; ++e) {
+      const int64_t v = t_col_idx[e];
+      if (v == u) continue;
+      const int64_t deg = (int64_t)deg_in[v] - 1;
+      const double inv = deg > 0 ? 1.0 / (double)deg : 0.0;
+      const double *a = dZ + v * d;
+      for (int64_t j = 0; j < d; ++j) g[j] += inv * a[j];
+    }
+    if (u >= n_in)
+      for (int64_t j = 0; j < d; ++j) g[j] *= s_halo;
+  }
+}

@@ -73,6 +73,10 @@ def lib():
                                      C.c_double, _f64p, _f32p, _f64p]
         L.bnso_aggregate_bwd.argtypes = [C.c_int64, C.c_int64, C.c_int64, _i32p, _i32p, _i32p, _i32p,
                                          _i32p, C.c_double, _f64p, _f64p, _f64p]
+        L.bnso_aggregate_mean.argtypes = [C.c_int64, C.c_int64, _i32p, _i32p, _i32p, _i32p, C.c_double,
+                                          _f64p, _f32p, _f64p]
+        L.bnso_aggregate_mean_bwd.argtypes = [C.c_int64, C.c_int64, C.c_int64, _i32p, _i32p, _i32p,
+                                              C.c_double, _f64p, _f64p, _f64p]
         _lib = L
     return _lib
 
@@ -216,6 +220,68 @@ def backward(part, sub, A, H, W, dZ_last, p):
     return dW, dhalo, dH
 
 
+# ---------------------------------------------------------------------------------------------
+# GraphSAGE with a mean aggregator (Section 2), the model of the paper's experiments:
+#   z_v = mean over the neighbours of v,  h'_v = sigma(W . CONCAT(z_v, h_v)),
+# with W of shape [2 d_in, d_out] = [W_n ; W_s] (neighbour half first).  Under boundary sampling
+# the kept boundary features are divided by p and the mean keeps the full-graph neighbour count
+# (Section 3.2), so that the estimate of z_v is unbiased.
+def aggregate_mean(part, row_ptr, col_idx, kept_ids, s_halo, H_in, halo_h):
+    n_in, d = H_in.shape
+    Z = np.empty((n_in, d), dtype=np.float64)
+    lib().bnso_aggregate_mean(n_in, d, row_ptr, _pad1(col_idx, np.int32), part.deg_in,
+                              _pad1(kept_ids, np.int32), float(s_halo),
+                              np.ascontiguousarray(H_in, dtype=np.float64), _pad1(halo_h, np.float32), Z)
+    return Z
+
+
+def aggregate_mean_bwd(part, t_row_ptr, t_col_idx, kept_ids, s_halo, dZ):
+    n_in, d = dZ.shape
+    n_u = kept_ids.shape[0]
+    dH = np.empty((n_in, d), dtype=np.float64)
+    dhalo = np.empty((max(n_u, 1), d), dtype=np.float64)
+    lib().bnso_aggregate_mean_bwd(n_in, n_u, d, t_row_ptr, _pad1(t_col_idx, np.int32), part.deg_in,
+                                  float(s_halo), np.ascontiguousarray(dZ, dtype=np.float64), dH, dhalo)
+    return dH, dhalo[:n_u]
+
+
+def forward_sage(part, sub, X, halo_h, W, p, Z_out=None):
+    """-> (A list, H list): A[l] = mean aggregate z of layer l, H[l] = ReLU([A[l] | H[l-1]] W[l])
+    for l < L, no ReLU on the last layer."""
+    L = len(W)
+    s = halo_scale(p, sub["kept_ids"].shape[0])
+    H = [np.asarray(X, dtype=np.float64)]
+    A = [None]
+    for l in range(1, L + 1):
+        a = aggregate_mean(part, sub["row_ptr"], sub["col_idx"], sub["kept_ids"], s, H[l - 1], halo_h[l - 1])
+        z = np.hstack([a, H[l - 1]]) @ np.asarray(W[l - 1], dtype=np.float64)
+        A.append(a)
+        H.append(np.maximum(z, 0.0) if l < L else z)
+        if Z_out is not None:
+            Z_out.append(z)
+    return A, H
+
+
+def backward_sage(part, sub, A, H, W, dZ_last, p):
+    L = len(W)
+    s = halo_scale(p, sub["kept_ids"].shape[0])
+    dW = [None] * L
+    dhalo = [None] * L
+    dH = [None] * (L + 1)
+    dZ = dZ_last
+    for l in range(L, 0, -1):
+        if l < L:
+            dZ = dH[l] * (H[l] > 0.0)
+        d_in = H[l - 1].shape[1]
+        dW[l - 1] = np.hstack([A[l], H[l - 1]]).T @ dZ
+        if l > 1:
+            dcat = dZ @ np.asarray(W[l - 1], dtype=np.float64).T      # [n_in, 2 d_in]
+            dh_nbr, dhalo[l - 1] = aggregate_mean_bwd(part, sub["t_row_ptr"], sub["t_col_idx"],
+                                                      sub["kept_ids"], s, np.ascontiguousarray(dcat[:, :d_in]))
+            dH[l - 1] = dh_nbr + dcat[:, d_in:]
+    return dW, dhalo, dH
+
+
 def sample_and_build(part, seed, epoch, p):
     kept_ids, remap = sample(seed, epoch, part.part_id, p, part.halo_gid)
     row_ptr, col_idx = induced_csr(part.n_in, part.row_ptr0, part.col0, remap)
@@ -224,13 +290,15 @@ def sample_and_build(part, seed, epoch, p):
                 t_row_ptr=t_row_ptr, t_col_idx=t_col_idx)
 
 
-def step(part, loss_kind, X, halo_h, labels, W, seed, epoch, p, lr=0.0):
-    """One iteration of Algorithm 1 on one partition (no exchange, optional SGD)."""
+def step(part, loss_kind, X, halo_h, labels, W, seed, epoch, p, lr=0.0, layer_kind=0):
+    """One iteration of Algorithm 1 on one partition (no exchange, optional SGD).
+    layer_kind 0: GCN layer of Appendix A; 1: GraphSAGE-mean layer of Section 2."""
     sub = sample_and_build(part, seed, epoch, p)
     Z = []
-    A, H = forward(part, sub, X, halo_h, W, p, Z_out=Z)
+    fwd, bwd = (forward, backward) if layer_kind == 0 else (forward_sage, backward_sage)
+    A, H = fwd(part, sub, X, halo_h, W, p, Z_out=Z)
     loss, dZ = loss_and_grad(H[-1], labels, loss_kind)
-    dW, dhalo, dH = backward(part, sub, A, H, W, dZ, p)
+    dW, dhalo, dH = bwd(part, sub, A, H, W, dZ, p)
     out = dict(sub=sub, A=A, H=H, Z=[None] + Z, loss=loss, dZ_last=dZ, dW=dW, dhalo=dhalo, dH=dH)
     if lr > 0.0:
         out["W_new"] = [np.asarray(w, dtype=np.float64) - lr * g for w, g in zip(W, dW)]
