@@ -74,6 +74,12 @@ typedef struct {
   const int32_t *dims;  /* host int32[L+1]: d_0 .. d_L (layer l maps d_{l-1} -> d_l)       */
   int32_t loss_kind;    /* 0: softmax cross-entropy, labels dev int32[n_in]
                            1: sigmoid binary cross-entropy, labels dev uint8[n_in*d_L]     */
+  int32_t layer_kind;   /* 0: GCN layer of Appendix A, H' = sigma(P H W), W f32[d_in*d_out]
+                           1: GraphSAGE with a mean aggregator (Section 2),
+                              H' = sigma([mean of neighbours | H] W), W f32[2*d_in*d_out] with
+                              the neighbour half first; kept boundary features are divided
+                              by p and the mean keeps the full-graph neighbour count
+                              (deg - 1 of the arrays below), Section 3.2                   */
 } bns_model_desc;
 
 /* Bytes of device workspace bns_create needs for this partition and model (sized for p = 1).
@@ -131,10 +137,12 @@ bns_status bns_gcn_layer_fwd(bns_ctx *ctx, int32_t layer, double p, const float 
  *   dW = A_saved^T dZ;  dA = dZ W^T;  [dH_in ; dhalo] = S^T P^T dA.
  *   dW dev f32[d_in*d_out] (out); dH_in dev f32[n_in*d_in] (out, or NULL to skip dA and the
  *   transposed aggregate, as for layer 1); dhalo dev f32[n_halo*d_in] (capacity; first *n_kept
- *   rows valid: gradient w.r.t. the unscaled features of the kept boundary nodes; NULL to skip). */
+ *   rows valid: gradient w.r.t. the unscaled features of the kept boundary nodes; NULL to skip).
+ * H_in (the layer's input, dev f32[n_in*d_in]) is read by the mean-aggregator layer only
+ * (dW = [A_saved | H_in]^T dZ, f32[2*d_in*d_out]); it may be NULL for the GCN layer. */
 bns_status bns_gcn_layer_bwd(bns_ctx *ctx, int32_t layer, double p, const float *dH_out,
-                             const float *H_out, const float *A_saved, const float *W, float *dW,
-                             float *dH_in, float *dhalo, void *stream);
+                             const float *H_out, const float *A_saved, const float *H_in,
+                             const float *W, float *dW, float *dH_in, float *dhalo, void *stream);
 
 /* One iteration of Algorithm 1 for this partition: sample, induced subgraph (+ transpose), L
  * layers forward, loss summed over inner nodes, backward, optional SGD w <- w - lr * g.

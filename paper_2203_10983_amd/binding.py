@@ -39,7 +39,8 @@ class PartitionDesc(C.Structure):
 
 
 class ModelDesc(C.Structure):
-    _fields_ = [("n_layers", C.c_int32), ("dims", C.POINTER(C.c_int32)), ("loss_kind", C.c_int32)]
+    _fields_ = [("n_layers", C.c_int32), ("dims", C.POINTER(C.c_int32)), ("loss_kind", C.c_int32),
+                ("layer_kind", C.c_int32)]
 
 
 class BnsError(RuntimeError):
@@ -77,7 +78,7 @@ def load_library():
     L.bns_gcn_layer_fwd.restype = i32
     L.bns_gcn_layer_fwd.argtypes = [vp, i32, f64, vp, vp, vp, vp, vp, i32, vp]
     L.bns_gcn_layer_bwd.restype = i32
-    L.bns_gcn_layer_bwd.argtypes = [vp, i32, f64, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.bns_gcn_layer_bwd.argtypes = [vp, i32, f64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.bns_train_step.restype = i32
     L.bns_train_step.argtypes = [vp, u64, u32, f64, vp, C.POINTER(vp), vp, C.POINTER(vp),
                                  C.POINTER(vp), C.POINTER(vp), vp, C.c_float, vp]
@@ -111,7 +112,7 @@ def _ptr_array(tensors):
 class Context:
     """Owns the device copies of one partition's static arrays, the workspace and the bns_ctx."""
 
-    def __init__(self, part, dims, loss_kind, device="cuda:0"):
+    def __init__(self, part, dims, loss_kind, device="cuda:0", layer_kind=0):
         L = load_library()
         if not torch.cuda.is_available():
             raise RuntimeError("the BNS-GCN library needs a GPU (there is no CPU fallback)")
@@ -133,7 +134,7 @@ class Context:
                                  s["halo_gid"].data_ptr(), s["deg_in"].data_ptr(),
                                  s["deg_halo"].data_ptr())
         self._dims_c = (C.c_int32 * len(dims))(*dims)
-        self._md = ModelDesc(self.n_layers, self._dims_c, loss_kind)
+        self._md = ModelDesc(self.n_layers, self._dims_c, loss_kind, layer_kind)
         self.ws_bytes = int(L.bns_workspace_bytes(C.byref(self._pd), C.byref(self._md)))
         if self.ws_bytes == 0:
             raise BnsError(1, "invalid partition or model descriptor")
@@ -173,10 +174,10 @@ class Context:
         self._check(self._lib.bns_gcn_layer_fwd(self._ctx, layer, p, _ptr(H_in), _ptr(halo_h), _ptr(W),
                                                 _ptr(A_saved), _ptr(H_out), int(relu), _stream()))
 
-    def gcn_layer_bwd(self, layer, p, dH_out, H_out, A_saved, W, dW, dH_in, dhalo):
+    def gcn_layer_bwd(self, layer, p, dH_out, H_out, A_saved, H_in, W, dW, dH_in, dhalo):
         self._check(self._lib.bns_gcn_layer_bwd(self._ctx, layer, p, _ptr(dH_out), _ptr(H_out),
-                                                _ptr(A_saved), _ptr(W), _ptr(dW), _ptr(dH_in),
-                                                _ptr(dhalo), _stream()))
+                                                _ptr(A_saved), _ptr(H_in), _ptr(W), _ptr(dW),
+                                                _ptr(dH_in), _ptr(dhalo), _stream()))
 
     def train_step(self, seed, epoch, p, X, halo_h, labels, W, dW, dhalo, loss, lr=0.0):
         self._check(self._lib.bns_train_step(

@@ -39,7 +39,8 @@ struct Layout {
   int32_t *tile_sums;
   uint64_t *ballots;
   int32_t *kpos, *hlen;
-  float *Hu, *G0, *G1, *partials, *loss_partials;
+  float *Hu, *G0, *G1, *G2, *partials, *loss_partials;
+  float *inv_deg;            // 1 / (full-graph degree) of the inner nodes, for the mean aggregator
   SegPlan plan_f, plan_b;   // segmentation of the static CSR and of the transposed inner block
   int32_t *seg_tmp_a, *seg_tmp_b;
   float *spmm_partials;
@@ -68,7 +69,7 @@ struct bns_ctx {
   Profiler prof;
   bns_partition_desc part;
   std::vector<int32_t> dims;
-  int32_t n_layers, loss_kind;
+  int32_t n_layers, loss_kind, layer_kind;
   Layout ws;
   // latest sample / subgraph the layer calls work on
   const int32_t *cur_kept = nullptr, *cur_remap = nullptr, *cur_n_kept = nullptr;
@@ -85,6 +86,7 @@ bool valid_desc(const bns_partition_desc *p, const bns_model_desc *m) {
   if (p->n_in < 1 || p->n_halo < 0 || p->nnz0 < p->n_in || p->e_in < p->n_in || p->e_bd < 0) return false;
   if (p->e_in + p->e_bd != p->nnz0) return false;
   if (m->n_layers < 1 || (m->loss_kind != 0 && m->loss_kind != 1)) return false;
+  if (m->layer_kind != 0 && m->layer_kind != 1) return false;
   for (int l = 0; l <= m->n_layers; ++l)
     if (m->dims[l] < 1 || m->dims[l] > 2048) return false;
   return true;
@@ -124,6 +126,8 @@ size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, La
   w.Hu = c.take<float>(B * d_in_max);
   w.G0 = c.take<float>(n_in * d_max);
   w.G1 = c.take<float>(n_in * d_max);
+  w.G2 = c.take<float>(n_in * d_max);
+  w.inv_deg = c.take<float>(n_in);
   w.partials = c.take<float>(part_max);
   w.loss_partials = c.take<float>(kLossBlocks);
   for (int k = 0; k < 2; ++k) {
@@ -196,14 +200,17 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
                           const float *W, float *A_saved, float *H_out, bool relu, hipStream_t s) {
   const int n_in = ctx->part.n_in, B = ctx->part.n_halo;
   const int d_in = ctx->dims[layer - 1], d_out = ctx->dims[layer];
+  const bool sage = ctx->layer_kind == 1;
   {
+    // GCN: rows pre-scaled by (1/p) d~^-1/2; mean aggregator: by 1/p only
     PhaseTimer t(ctx, BNS_PHASE_GATHER, s);
-    BNS_TRY("halo_gather", halo_gather(halo_h, ctx->cur_kept, ctx->cur_n_kept, B, ctx->ws.dis_halo,
-                                       halo_scale(p), d_in, ctx->ws.Hu, s));
+    BNS_TRY("halo_gather", halo_gather(halo_h, ctx->cur_kept, ctx->cur_n_kept, B,
+                                       sage ? nullptr : ctx->ws.dis_halo, halo_scale(p), d_in, ctx->ws.Hu, s));
   }
   {
     PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
     SpmmRowPart part;
+    part.skip_self = sage;
     if (layer == 1 && ctx->cache_X != nullptr && ctx->cache_X == H_in) {
       // inner neighbours are the same every epoch: their sum is cached, only the kept boundary
       // tail of each row is aggregated now
@@ -211,22 +218,51 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
       part.init = ctx->ws.C0;
     }
     BNS_TRY("spmm_fwd", spmm_fwd(ctx->ws.plan_f, n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx,
-                                 ctx->ws.dis_in, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part, s));
+                                 sage ? nullptr : ctx->ws.dis_in, sage ? ctx->ws.inv_deg : ctx->ws.dis_in,
+                                 H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part, s));
   }
   {
     PhaseTimer t(ctx, BNS_PHASE_GEMM_FWD, s);
-    BNS_TRY("gemm_nn", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, relu, s));
+    if (!sage) {
+      BNS_TRY("gemm_nn", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, relu, false, s));
+    } else {  // [z | h] [W_n ; W_s] = z W_n + h W_s
+      BNS_TRY("gemm_nn(nbr)", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, false, false, s));
+      BNS_TRY("gemm_nn(self)", gemm_nn(n_in, d_out, d_in, H_in, W + (size_t)d_in * d_out, H_out, relu, true, s));
+    }
   }
   return BNS_OK;
 }
 
 // dZ is the gradient of the layer's pre-activation.  mask_src (nullable): activations of the
 // layer below; when given, dH_in receives the masked gradient (= dZ of the layer below).
+// H_in is needed by the mean-aggregator layer only (its self half of the weight gradient).
 bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, const float *A_saved,
-                          const float *W, float *dW, float *dH_in, float *dhalo,
+                          const float *H_in, const float *W, float *dW, float *dH_in, float *dhalo,
                           const float *mask_src, hipStream_t s) {
   const int n_in = ctx->part.n_in, B = ctx->part.n_halo;
   const int d_in = ctx->dims[layer - 1], d_out = ctx->dims[layer];
+  if (ctx->layer_kind == 1) {
+    const size_t half = (size_t)d_in * d_out;
+    {
+      PhaseTimer t(ctx, BNS_PHASE_GEMM_DW, s);
+      BNS_TRY("gemm_tn_splitk(nbr)", gemm_tn_splitk(d_in, d_out, n_in, A_saved, dZ, dW, ctx->ws.partials, s));
+      BNS_TRY("gemm_tn_splitk(self)", gemm_tn_splitk(d_in, d_out, n_in, H_in, dZ, dW + half, ctx->ws.partials, s));
+    }
+    if (dH_in) {
+      {
+        PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
+        BNS_TRY("gemm_nt(nbr)", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, nullptr, nullptr, s));
+        BNS_TRY("gemm_nt(self)", gemm_nt(n_in, d_in, d_out, dZ, W + half, ctx->ws.G2, nullptr, nullptr, s));
+      }
+      // dH_in = (gradient through the node's own feature) + mean^T (gradient of the neighbour mean)
+      PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
+      BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_in, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
+                                   ctx->cur_kept, ctx->cur_n_kept, ctx->ws.inv_deg, nullptr, nullptr,
+                                   halo_scale(p), ctx->ws.G1, mask_src, ctx->ws.G2, true,
+                                   ctx->ws.spmm_partials, dH_in, dhalo, s));
+    }
+    return BNS_OK;
+  }
   {
     PhaseTimer t(ctx, BNS_PHASE_GEMM_DW, s);
     BNS_TRY("gemm_tn_splitk", gemm_tn_splitk(d_in, d_out, n_in, A_saved, dZ, dW, ctx->ws.partials, s));
@@ -237,8 +273,9 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
     {
       PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
       BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_out, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
-                                   ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_halo,
-                                   halo_scale(p), dZ, nullptr, ctx->ws.spmm_partials, G_in, G_halo, s));
+                                   ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_in,
+                                   ctx->ws.dis_halo, halo_scale(p), dZ, nullptr, nullptr, false,
+                                   ctx->ws.spmm_partials, G_in, G_halo, s));
     }
     PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
     BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, G_in, W, dH_in, mask_src, nullptr, s));
@@ -251,8 +288,9 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
     }
     PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
     BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_in, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
-                                 ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_halo,
-                                 halo_scale(p), ctx->ws.G1, mask_src, ctx->ws.spmm_partials, dH_in, dhalo, s));
+                                 ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_in,
+                                 ctx->ws.dis_halo, halo_scale(p), ctx->ws.G1, mask_src, nullptr, false,
+                                 ctx->ws.spmm_partials, dH_in, dhalo, s));
   }
   return BNS_OK;
 }
@@ -313,6 +351,7 @@ bns_status bns_create(bns_ctx **out, const bns_partition_desc *part, const bns_m
   ctx->part = *part;
   ctx->n_layers = model->n_layers;
   ctx->loss_kind = model->loss_kind;
+  ctx->layer_kind = model->layer_kind;
   ctx->dims.assign(model->dims, model->dims + model->n_layers + 1);
   Carver c(dev_ws);
   const size_t need = carve(c, part, model, &ctx->ws);
@@ -320,6 +359,7 @@ bns_status bns_create(bns_ctx **out, const bns_partition_desc *part, const bns_m
   *out = ctx;  // handed out even if set-up fails, so that the caller can read the error text
   hipStream_t s = static_cast<hipStream_t>(stream);
   BNS_TRY("degree_rsqrt(in)", degree_rsqrt(part->deg_in, part->n_in, ctx->ws.dis_in, s));
+  BNS_TRY("degree_inverse", degree_inverse(part->deg_in, part->n_in, ctx->ws.inv_deg, s));
   BNS_TRY("degree_rsqrt(halo)", degree_rsqrt(part->deg_halo, part->n_halo, ctx->ws.dis_halo, s));
   BNS_TRY("build_static_split", build_static_split(part->n_in, part->row_ptr0, part->col0, ctx->ws.split,
                                                    ctx->ws.tile_sums, s));
@@ -366,12 +406,13 @@ bns_status bns_gcn_layer_fwd(bns_ctx *ctx, int32_t layer, double p, const float 
 }
 
 bns_status bns_gcn_layer_bwd(bns_ctx *ctx, int32_t layer, double p, const float *dH_out, const float *H_out,
-                             const float *A_saved, const float *W, float *dW, float *dH_in, float *dhalo,
-                             void *stream) {
+                             const float *A_saved, const float *H_in, const float *W, float *dW, float *dH_in,
+                             float *dhalo, void *stream) {
   if (!ctx) return BNS_EINVAL;
   if (layer < 1 || layer > ctx->n_layers) return fail(ctx, BNS_EINVAL, "layer out of range");
   if (bad_p(p)) return fail(ctx, BNS_EINVAL, "p must lie in [0, 1]");
   if (!dH_out || !A_saved || !W || !dW) return fail(ctx, BNS_EINVAL, "null pointer");
+  if (ctx->layer_kind == 1 && !H_in) return fail(ctx, BNS_EINVAL, "the mean-aggregator layer needs H_in");
   if (!dH_in && dhalo) return fail(ctx, BNS_EINVAL, "dhalo needs dH_in");
   if (!ctx->cur_t_row_ptr) return fail(ctx, BNS_EINVAL, "bns_build_sampled_csr has not been called");
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -381,7 +422,7 @@ bns_status bns_gcn_layer_bwd(bns_ctx *ctx, int32_t layer, double p, const float 
     BNS_TRY("relu_mask", relu_mask(n, dH_out, H_out, ctx->ws.G0, s));
     dZ = ctx->ws.G0;
   }
-  return layer_bwd_impl(ctx, layer, p, dZ, A_saved, W, dW, dH_in, dhalo, nullptr, s);
+  return layer_bwd_impl(ctx, layer, p, dZ, A_saved, H_in, W, dW, dH_in, dhalo, nullptr, s);
 }
 
 bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p, const float *X,
@@ -425,14 +466,16 @@ bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
   // masked by the activations of the layer below
   for (int l = L; l >= 1; --l) {
     float *dh = (dhalo && l > 1) ? dhalo[l - 1] : nullptr;
-    st = layer_bwd_impl(ctx, l, p, w.G0, w.A[l], W[l - 1], dW[l - 1], l > 1 ? w.G0 : nullptr, dh,
+    st = layer_bwd_impl(ctx, l, p, w.G0, w.A[l], l > 1 ? w.H[l - 1] : X, W[l - 1], dW[l - 1],
+                        l > 1 ? w.G0 : nullptr, dh,
                         l > 1 ? w.H[l - 1] : nullptr, s);
     if (st != BNS_OK) return st;
   }
   if (lr > 0.f) {
     PhaseTimer t(ctx, BNS_PHASE_SGD, s);
     for (int l = 0; l < L; ++l)
-      BNS_TRY("sgd_update", sgd_update((int64_t)ctx->dims[l] * ctx->dims[l + 1], W[l], dW[l], lr, s));
+      BNS_TRY("sgd_update", sgd_update((int64_t)(ctx->layer_kind == 1 ? 2 : 1) * ctx->dims[l] * ctx->dims[l + 1], W[l],
+                                       dW[l], lr, s));
   }
   return BNS_OK;
 }
@@ -442,13 +485,15 @@ bns_status bns_cache_input_aggregate(bns_ctx *ctx, const float *X, void *stream)
   ctx->cache_X = nullptr;
   if (!X) return BNS_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  // C0[v,:] = sum over the inner neighbours u of v of d~_u^-1/2 X[u,:]  (static CSR, inner entries only)
+  // C0[v,:] = sum over the inner neighbours u of v of d~_u^-1/2 X[u,:] (GCN layer) or of X[u,:]
+  // without the self-loop (mean aggregator): static CSR, inner entries only, no row factor
+  const bool sage = ctx->layer_kind == 1;
   SpmmRowPart part;
   part.row_take = ctx->ws.split.n_inner;
-  part.unscaled = true;
+  part.skip_self = sage;
   BNS_TRY("spmm_fwd(cache)", spmm_fwd(ctx->ws.plan_f, ctx->part.n_in, ctx->dims[0], ctx->part.row_ptr0,
-                                      ctx->part.col0, ctx->ws.dis_in, X, nullptr, ctx->ws.spmm_partials,
-                                      ctx->ws.C0, part, s));
+                                      ctx->part.col0, sage ? nullptr : ctx->ws.dis_in, nullptr, X, nullptr,
+                                      ctx->ws.spmm_partials, ctx->ws.C0, part, s));
   ctx->cache_X = X;
   return BNS_OK;
 }

@@ -68,6 +68,17 @@ degree_rsqrt_kernel(const int32_t *__restrict__ deg, int32_t n, float *__restric
   if (i < n) dis[i] = 1.0f / sqrtf((float)deg[i]);
 }
 
+__global__ void __launch_bounds__(kThreads)
+degree_inverse_kernel(const int32_t *__restrict__ deg, int32_t n, float *__restrict__ inv) {
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  if (i < n) inv[i] = deg[i] > 1 ? 1.0f / (float)(deg[i] - 1) : 0.f;
+}
+
+hipError_t degree_inverse(const int32_t *deg, int32_t n, float *inv, hipStream_t s) {
+  if (n > 0) degree_inverse_kernel<<<(n + kThreads - 1) / kThreads, kThreads, 0, s>>>(deg, n, inv);
+  return hipGetLastError();
+}
+
 hipError_t degree_rsqrt(const int32_t *deg, int32_t n, float *dis, hipStream_t s) {
   if (n > 0) degree_rsqrt_kernel<<<(n + kThreads - 1) / kThreads, kThreads, 0, s>>>(deg, n, dis);
   return hipGetLastError();

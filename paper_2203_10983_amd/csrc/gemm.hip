@@ -98,7 +98,8 @@ __device__ __forceinline__ void store_ncontig(const FragN<COLS> &f, float *__res
   }
 }
 
-// EPI: 0 = store, 1 = ReLU, 2 = zero where mask_src <= 0 (ReLU mask of the backward pass).
+// EPI: 0 = store, 1 = ReLU, 2 = zero where mask_src <= 0 (ReLU mask of the backward pass),
+// 3 = add to C, 4 = add to C then ReLU.
 // m_dev (nullable): the row count lives on the device (*m_dev <= M); tiles past it do nothing.
 template <int BN, bool A_KCONTIG, bool B_KCONTIG, int EPI>
 __global__ void __launch_bounds__(kGemmThreads)
@@ -187,7 +188,8 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
         const int row = bm0 + wm + i * 32 + (r >> 2) * 8 + lhi * 4 + (r & 3);
         if (row < M) {
           float x = acc[i][j][r];
-          if (EPI == 1) x = fmaxf(x, 0.f);
+          if (EPI == 3 || EPI == 4) x += C[(size_t)row * ldc + col];
+          if (EPI == 1 || EPI == 4) x = fmaxf(x, 0.f);
           if (EPI == 2) x = mask_src[(size_t)row * ldc + col] > 0.f ? x : 0.f;
           C[(size_t)row * ldc + col] = x;
         }
@@ -213,13 +215,15 @@ static inline unsigned n_tiles(int M, int N, int bn) {
   } while (0)
 
 hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   bool relu, hipStream_t s) {
+                   bool relu, bool accumulate, hipStream_t s) {
   const int bn = pick_bn(N);
   const unsigned tiles = n_tiles(M, N, bn);
   if (tiles == 0) return hipSuccess;
   const bool va = (K % 4 == 0) && aligned16(A), vb = (N % 4 == 0) && aligned16(B);
   const dim3 grid(tiles, 1);
-  if (relu) BNS_GEMM_LAUNCH(true, false, 1, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, nullptr);
+  if (accumulate && relu) BNS_GEMM_LAUNCH(true, false, 4, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, nullptr);
+  else if (accumulate) BNS_GEMM_LAUNCH(true, false, 3, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, nullptr);
+  else if (relu) BNS_GEMM_LAUNCH(true, false, 1, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, nullptr);
   else BNS_GEMM_LAUNCH(true, false, 0, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, nullptr);
   return hipGetLastError();
 }

@@ -74,37 +74,42 @@ inline int64_t seg_max_multi(int64_t nnz) { return nnz / kSegLen + 1; }
 hipError_t build_seg_plan(int32_t n_rows, const int32_t *row_ptr, SegPlan *plan, int32_t *tmp_a,
                           int32_t *tmp_b, int32_t *tile_sums, hipStream_t s);
 
-// Hu[r,:] = (s_halo * dis_halo[b]) * halo_h[b,:], b = kept_ids[r], r < *n_kept.
+// Hu[r,:] = (s_halo * dis_halo[b]) * halo_h[b,:], b = kept_ids[r], r < *n_kept (dis_halo nullable = 1).
 hipError_t halo_gather(const float *halo_h, const int32_t *kept_ids, const int32_t *n_kept,
                        int32_t n_halo, const float *dis_halo, float s_halo, int32_t d, float *Hu,
                        hipStream_t s);
-// A[v,:] = dis_in[v] * ( sum_{u<n_in in row v} dis_in[u] H_in[u,:] + sum_{kept r in row v} Hu[r,:] )
-// plan: segmentation of the static local CSR; partials: scratch f32[plan.n_part * d].
-// part (all optional) restricts every row to entries [skip, skip+take) of its list, adds an
-// initial row vector before scaling, or leaves out the dis_in[v] row factor.
+// A[v,:] = row_scale[v] * ( init[v,:] + sum_{u<n_in in row v} w_col[u] H_in[u,:] + sum_{kept r in row v} Hu[r,:] )
+// w_col / row_scale nullable (= 1).  GCN layer: both = d~^-1/2; mean aggregator: w_col = null,
+// row_scale = 1/degree, skip_self.  plan: segmentation of the static local CSR; partials: scratch
+// f32[plan.n_part * d].  part (all optional) restricts every row to entries [skip, skip+take) of
+// its list, adds the initial row vector, or skips the stored self-loop.
 struct SpmmRowPart {
   const int32_t *row_skip = nullptr;
   const int32_t *row_take = nullptr;
   const float *init = nullptr;
-  bool unscaled = false;
+  bool skip_self = false;
 };
 hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
-                    const int32_t *col_idx, const float *dis_in, const float *H_in, const float *Hu,
-                    float *partials, float *A, const SpmmRowPart &part, hipStream_t s);
-// For stacked column u < n_in + *n_kept:  g = sum_{v in t_row u} dis_in[v] dA[v,:];
-//   u <  n_in: dH_in[u,:] = dis_in[u] * g   (zeroed where mask_src[u,:] <= 0 if mask_src != null)
+                    const int32_t *col_idx, const float *w_col, const float *row_scale,
+                    const float *H_in, const float *Hu, float *partials, float *A,
+                    const SpmmRowPart &part, hipStream_t s);
+// For stacked column u < n_in + *n_kept:  g = sum_{v in t_row u} w_col[v] dA[v,:];
+//   u <  n_in: dH_in[u,:] = row_scale[u] * (init[u,:] + g)  (zeroed where mask_src[u,:] <= 0 if given)
 //   u >= n_in: dhalo[u-n_in,:] = s_halo * dis_halo[kept_ids[u-n_in]] * g   (skipped if dhalo null)
-// plan: segmentation of the transposed inner-inner block (rows of kept boundary nodes are short).
+// row_scale, dis_halo, init nullable.  plan: segmentation of the transposed inner-inner block.
 hipError_t spmm_bwd(const SegPlan &plan, int32_t n_in, int32_t n_halo, int32_t d,
                     const int32_t *t_row_ptr, const int32_t *t_col_idx, const int32_t *kept_ids,
-                    const int32_t *n_kept, const float *dis_in, const float *dis_halo, float s_halo,
-                    const float *dA, const float *mask_src, float *partials, float *dH_in,
-                    float *dhalo, hipStream_t s);
+                    const int32_t *n_kept, const float *w_col, const float *row_scale,
+                    const float *dis_halo, float s_halo, const float *dA, const float *mask_src,
+                    const float *init, bool skip_self, float *partials, float *dH_in, float *dhalo,
+                    hipStream_t s);
 
 // ---- gemm.hip (Eq. 2 and its backward; fp32 MFMA) ----------------------------------------------
-// C[M,N] = A[M,K] B[K,N], optional ReLU.
+// C[M,N] = A[M,K] B[K,N] (+ the previous C if accumulate), then optional ReLU.
 hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   bool relu, hipStream_t s);
+                   bool relu, bool accumulate, hipStream_t s);
+// inv[i] = deg[i] > 1 ? 1 / (deg[i] - 1) : 0   (deg counts the self-loop)
+hipError_t degree_inverse(const int32_t *deg, int32_t n, float *inv, hipStream_t s);
 // C[M,N] = A[M,K] B[N,K]^T.  mask_src (nullable, [M,N]): C is zeroed where mask_src <= 0.
 // m_dev (nullable): device-side row count, *m_dev <= M; rows past it are not touched.
 hipError_t gemm_nt(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,

@@ -52,6 +52,7 @@ struct SpmmArgs {
   const int32_t *row_skip;     // skip the first row_skip[row] entries (nullable)
   const int32_t *row_take;     // then use row_take[row] entries instead of the rest (nullable)
   const float *init;           // out0 row = scale * (init row + sum) (nullable)
+  bool skip_self;              // entries with column == row contribute nothing (mean aggregator)
 };
 
 // Scale, optional ReLU mask and store of one finished row slice held as acc[c][i].
@@ -72,7 +73,7 @@ __device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, i
   } else {
     if (a.out1 == nullptr) return;
     const int r = row - a.n_split;
-    scale = a.s_halo * a.dis_halo[a.kept_ids[r]];
+    scale = a.dis_halo ? a.s_halo * a.dis_halo[a.kept_ids[r]] : a.s_halo;
     out = a.out1 + (size_t)r * d;
   }
 #pragma unroll
@@ -149,7 +150,8 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
       const int c = a.col_idx[base + lane];
       if (c < a.n_split) {
         p_l = (unsigned long long)(a.src0 + (size_t)c * d);
-        w_l = a.w_col[c];
+        w_l = a.w_col ? a.w_col[c] : 1.f;
+        if (a.skip_self && c == row) w_l = 0.f;  // the stored self-loop is not a neighbour
       } else {
         p_l = (unsigned long long)(a.src1 + (size_t)(c - a.n_split) * d);
         w_l = 1.f;
@@ -298,30 +300,34 @@ static hipError_t launch_spmm(const SpmmArgs &a, int64_t max_units, hipStream_t 
 }
 
 hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
-                    const int32_t *col_idx, const float *dis_in, const float *H_in, const float *Hu,
-                    float *partials, float *A, const SpmmRowPart &part, hipStream_t s) {
+                    const int32_t *col_idx, const float *w_col, const float *row_scale,
+                    const float *H_in, const float *Hu, float *partials, float *A,
+                    const SpmmRowPart &part, hipStream_t s) {
   SpmmArgs a{};
   a.plan = plan; a.n_extra_dev = nullptr; a.d = d;
   a.row_ptr = row_ptr; a.col_idx = col_idx; a.n_split = n_in;
-  a.src0 = H_in; a.src1 = Hu; a.w_col = dis_in; a.partials = partials;
-  a.out0 = A; a.out1 = nullptr; a.out_scale0 = part.unscaled ? nullptr : dis_in; a.mask_src = nullptr;
+  a.src0 = H_in; a.src1 = Hu; a.w_col = w_col; a.partials = partials;
+  a.out0 = A; a.out1 = nullptr; a.out_scale0 = row_scale; a.mask_src = nullptr;
   a.kept_ids = nullptr; a.dis_halo = nullptr; a.s_halo = 0.f;
   a.row_skip = part.row_skip; a.row_take = part.row_take; a.init = part.init;
+  a.skip_self = part.skip_self;
   return launch_spmm(a, plan.n_seg, s);
 }
 
 hipError_t spmm_bwd(const SegPlan &plan, int32_t n_in, int32_t n_halo, int32_t d,
                     const int32_t *t_row_ptr, const int32_t *t_col_idx, const int32_t *kept_ids,
-                    const int32_t *n_kept, const float *dis_in, const float *dis_halo, float s_halo,
-                    const float *dA, const float *mask_src, float *partials, float *dH_in,
-                    float *dhalo, hipStream_t s) {
+                    const int32_t *n_kept, const float *w_col, const float *row_scale,
+                    const float *dis_halo, float s_halo, const float *dA, const float *mask_src,
+                    const float *init, bool skip_self, float *partials, float *dH_in, float *dhalo,
+                    hipStream_t s) {
   SpmmArgs a{};
   const bool halo_rows = dhalo && n_halo > 0;
   a.plan = plan; a.n_extra_dev = halo_rows ? n_kept : nullptr; a.d = d;
   a.row_ptr = t_row_ptr; a.col_idx = t_col_idx; a.n_split = n_in;
-  a.src0 = dA; a.src1 = nullptr; a.w_col = dis_in; a.partials = partials;
-  a.out0 = dH_in; a.out1 = dhalo; a.out_scale0 = dis_in; a.mask_src = mask_src;
+  a.src0 = dA; a.src1 = nullptr; a.w_col = w_col; a.partials = partials;
+  a.out0 = dH_in; a.out1 = dhalo; a.out_scale0 = row_scale; a.mask_src = mask_src;
   a.kept_ids = kept_ids; a.dis_halo = dis_halo; a.s_halo = s_halo;
+  a.init = init; a.skip_self = skip_self;
   return launch_spmm(a, (int64_t)plan.n_seg + (halo_rows ? n_halo : 0), s);
 }
 
@@ -401,7 +407,7 @@ halo_gather_kernel(const float *__restrict__ halo_h, const int32_t *__restrict__
   const int waves = gridDim.x * 4;
   for (int r = blockIdx.x * 4 + (threadIdx.x >> 6); r < n; r += waves) {
     const int b = kept_ids[r];
-    const float sc = s_halo * dis_halo[b];
+    const float sc = dis_halo ? s_halo * dis_halo[b] : s_halo;
     const V *src = reinterpret_cast<const V *>(halo_h + (size_t)b * d);
     V *dst = reinterpret_cast<V *>(Hu + (size_t)r * d);
     for (int iv = lane; iv < nvec; iv += kWave) {

@@ -85,8 +85,9 @@ def test_null_context_is_rejected_everywhere(pkg):
     assert lib.bns_sample_boundary(None, 1, 0, 0.5, None, None, None, None) == 1
     assert lib.bns_build_sampled_csr(None, None, None, None, None, None, None) == 1
     assert lib.bns_gcn_layer_fwd(None, 1, 0.5, None, None, None, None, None, 1, None) == 1
-    assert lib.bns_gcn_layer_bwd(None, 1, 0.5, None, None, None, None, None, None, None, None) == 1
+    assert lib.bns_gcn_layer_bwd(None, 1, 0.5, None, None, None, None, None, None, None, None, None) == 1
     assert lib.bns_train_step(None, 1, 0, 0.5, None, None, None, None, None, None, None, 0.0, None) == 1
+    assert lib.bns_cache_input_aggregate(None, None, None) == 1
     assert lib.bns_profile_enable(None, 0, 0) == 1
     assert lib.bns_last_error(None) == b"null context"
     lib.bns_destroy(None)

@@ -32,7 +32,11 @@ FULL = [(2, 1, [1.0, 0.1, 0.01], 0), (3, 1, [0.1], 0), (4, 1, [0.1], 0), (5, 1, 
 # degenerate shapes (tests/edge_workloads.py): empty boundary, hub rows, one node, odd widths
 EDGES = [("e-nobd", 1, [0.5, 1.0], 0), ("e-star", 1, [0.5, 0.0, 1.0], 1), ("e-single", 1, [0.5, 0.0, 1.0], 2),
          ("e-wide", 1, [0.5], 3)]
-CASES = [(c, s, p, e) for (c, s, ps, e) in EDGES + SMALL + FULL for p in ps]
+# the same matrix for the GraphSAGE-mean layer (layer_kind 1), thinner
+SAGE = [(1, 1, [0.1, 1.0, 0.0], 0), ("e-star", 1, [0.5], 1), ("e-wide", 1, [0.5], 3), (2, 16, [0.1], 1),
+        (3, 32, [0.1], 2), (4, 16, [0.1], 3), (5, 1, [0.1], 0)]
+CASES = [(c, s, p, e, 0) for (c, s, ps, e) in EDGES + SMALL + FULL for p in ps] + \
+        [(c, s, p, e, 1) for (c, s, ps, e) in SAGE for p in ps]
 
 
 def _log(msg):
@@ -45,15 +49,19 @@ class _Case:
     key = None
     inst = None
 
-    def __init__(self, cfg, scale):
+    def __init__(self, cfg, scale, kind):
         import torch
         import paper_2203_10983_amd as pkg
+        from bns_inputs.workloads import sage_weights
         self.torch, self.pkg = torch, pkg
+        self.kind = kind
         self.w = EDGE[cfg]() if isinstance(cfg, str) else make_workload(cfg, scale=scale)
         w = self.w
+        if kind == 1:
+            w.W = sage_weights(77, w.dims)
         dev = torch.device("cuda:0")
         self.dev = dev
-        self.ctx = pkg.Context(w.part, w.dims, w.loss_kind, device=dev)
+        self.ctx = pkg.Context(w.part, w.dims, w.loss_kind, device=dev, layer_kind=kind)
         self.X = torch.from_numpy(w.X).to(dev)
         self.halo_h = [torch.from_numpy(h).to(dev) for h in w.halo_h]
         self.labels = torch.from_numpy(w.labels).to(dev)
@@ -61,15 +69,15 @@ class _Case:
         self.ref = {}
 
     @classmethod
-    def get(cls, cfg, scale):
-        if cls.key != (cfg, scale):
+    def get(cls, cfg, scale, kind):
+        if cls.key != (cfg, scale, kind):
             if cls.inst is not None:
                 cls.inst.ctx.close()
             cls.inst = None
             cls.key = None
-            _log(f"[case] building cfg={cfg} scale={scale}")
-            cls.inst = cls(cfg, scale)
-            cls.key = (cfg, scale)
+            _log(f"[case] building cfg={cfg} scale={scale} layer_kind={kind}")
+            cls.inst = cls(cfg, scale, kind)
+            cls.key = (cfg, scale, kind)
             P = cls.inst.w.part
             _log(f"[case] n_in={P.n_in} n_halo={P.n_halo} nnz0={P.nnz0} dims={cls.inst.w.dims}")
         return cls.inst
@@ -79,17 +87,17 @@ class _Case:
             self.ref.clear()
             w = self.w
             self.ref[(p, epoch)] = orc.step(w.part, w.loss_kind, w.X, w.halo_h, w.labels, w.W,
-                                            SAMPLING_SEED, epoch, p)
+                                            SAMPLING_SEED, epoch, p, layer_kind=self.kind)
         return self.ref[(p, epoch)]
 
     def f32(self, a):
         return self.torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev)
 
 
-@pytest.fixture(scope="module", params=CASES, ids=lambda c: f"cfg{c[0]}-s{c[1]}-p{c[2]}-")
+@pytest.fixture(scope="module", params=CASES, ids=lambda c: f"{'sage' if c[4] else 'gcn'}-cfg{c[0]}-s{c[1]}-p{c[2]}-")
 def case(request):
-    cfg, scale, p, epoch = request.param
-    return _Case.get(cfg, scale), p, epoch
+    cfg, scale, p, epoch, kind = request.param
+    return _Case.get(cfg, scale, kind), p, epoch
 
 
 def _sample_and_build(c, p, epoch):
@@ -150,10 +158,10 @@ def test_layers_with_oracle_activations(case):
         # backward of the same layer from the oracle's upstream gradient and activations
         dH_out = c.f32(ref["dZ_last"] if l == L else ref["dH"][l])
         H_ref = None if l == L else c.f32(ref["H"][l])
-        dW = torch.empty(d_in, d_out, dtype=torch.float32, device=c.dev)
+        dW = torch.empty_like(c.W[l - 1])
         dH_in = torch.empty(P.n_in, d_in, dtype=torch.float32, device=c.dev) if l > 1 else None
         dhalo = torch.full((P.n_halo + 1, d_in), 7.0, dtype=torch.float32, device=c.dev) if l > 1 else None
-        c.ctx.gcn_layer_bwd(l, p, dH_out, H_ref, c.f32(ref["A"][l]), c.W[l - 1], dW, dH_in, dhalo)
+        c.ctx.gcn_layer_bwd(l, p, dH_out, H_ref, c.f32(ref["A"][l]), H_in, c.W[l - 1], dW, dH_in, dhalo)
         torch.cuda.synchronize()
         worst = max(worst, assert_close(dW.cpu().numpy(), ref["dW"][l - 1], f"dW[{l}]"))
         if l > 1:
@@ -205,10 +213,11 @@ def test_train_step_end_to_end(case):
         A_l = view(pkg.VIEW_A, l, torch.float32).view(P.n_in, d_in).clone()
         if l == L:  # gradient of the loss by the oracle's formula on the step's own logits
             g = c.f32(orc.loss_and_grad(H_l.cpu().numpy(), w.labels, w.loss_kind)[1])
-        dWl = torch.empty(d_in, d_out, **f32)
+        dWl = torch.empty_like(c.W[l - 1])
         dH_in = torch.empty(P.n_in, d_in, **f32) if l > 1 else None
         dh = torch.zeros(P.n_halo + 1, d_in, **f32) if l > 1 else None
-        c.ctx.gcn_layer_bwd(l, p, g, None if l == L else H_l, A_l, c.W[l - 1], dWl, dH_in, dh)
+        H_below = c.X if l == 1 else view(pkg.VIEW_H, l - 1, torch.float32).view(P.n_in, d_in).clone()
+        c.ctx.gcn_layer_bwd(l, p, g, None if l == L else H_l, A_l, H_below, c.W[l - 1], dWl, dH_in, dh)
         torch.cuda.synchronize()
         assert rel_err(dW[l - 1].cpu().numpy(), dWl.cpu().numpy()) <= 5e-5, f"dW[{l}] vs chained layers"
         if l > 1:
