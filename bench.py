@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=5, help="config 1..5 of BASELINE.json")
     ap.add_argument("--p", type=float, default=None, help="sampling rate (default: the config's first)")
+    ap.add_argument("--model", choices=["gcn", "sage"], default="gcn",
+                    help="gcn: the GCN layer of the five configs; sage: GraphSAGE-mean, the paper's own model")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-input-cache", action="store_true",
                     help="do not install the static inner aggregate of layer 1 (bns_cache_input_aggregate)")
@@ -45,14 +47,18 @@ def main():
     import torch
     import paper_2203_10983_amd as pkg
     from bns_inputs import SAMPLING_SEED, make_workload
+    from bns_inputs.workloads import sage_weights
 
     t0 = time.time()
     w = make_workload(args.workload)
+    kind = 1 if args.model == "sage" else 0
+    if kind == 1:
+        w.W = sage_weights(220310983 + w.cfg + 300, w.dims)
     P = w.part
     p = args.p if args.p is not None else 0.1
     L = w.n_layers
     dev = torch.device("cuda:0")
-    ctx = pkg.Context(P, w.dims, w.loss_kind, device=dev)
+    ctx = pkg.Context(P, w.dims, w.loss_kind, device=dev, layer_kind=kind)
     X = torch.from_numpy(w.X).to(dev)
     halo_h = [torch.from_numpy(h).to(dev) for h in w.halo_h]
     labels = torch.from_numpy(w.labels).to(dev)
@@ -107,9 +113,10 @@ def main():
         fwd_bytes += -(4 * nnz + 4 * dims[0] * (n_in + n_kept)) + 4 * e_u + 4 * dims[0] * (n_in + n_kept)
     bwd_bytes = sum(4 * nnz + 4 * (n_in + n_kept + 1) + 4 * dims[l - 1] * n_in
                     + 4 * dims[l - 1] * (n_in + n_kept) for l in range(2, L + 1))
-    gemm_flops = {"gemm_fwd": sum(2 * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1)),
-                  "gemm_dw": sum(2 * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1)),
-                  "gemm_da": sum(2 * n_in * dims[l - 1] * dims[l] for l in range(2, L + 1))}
+    kw = 2 if kind == 1 else 1      # the concat update doubles the depth of every product
+    gemm_flops = {"gemm_fwd": sum(2 * kw * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1)),
+                  "gemm_dw": sum(2 * kw * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1)),
+                  "gemm_da": sum(2 * kw * n_in * dims[l - 1] * dims[l] for l in range(2, L + 1))}
     per_step_ms = {k: v[0] / args.steps for k, v in phases.items()}
     launches = {k: v[1] // args.steps for k, v in phases.items()}
     cand = {k: per_step_ms[k] for k in ("spmm_fwd", "spmm_bwd", "gemm_fwd", "gemm_dw", "gemm_da")}
@@ -149,7 +156,7 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import bns_oracle as orc
         tc = time.perf_counter()
-        ref = orc.step(P, w.loss_kind, w.X, w.halo_h, w.labels, w.W, SAMPLING_SEED, 0, p)
+        ref = orc.step(P, w.loss_kind, w.X, w.halo_h, w.labels, w.W, SAMPLING_SEED, 0, p, layer_kind=kind)
         dt = time.perf_counter() - tc
         nnz0 = int(ref["sub"]["col_idx"].size)
         cpu = {"value": nnz0 * (2 * L - 1) / dt, "unit": "edges/s", "cores": orc.num_threads(),
@@ -165,7 +172,8 @@ def main():
                    "n_kept": n_kept, "nnz": nnz, "dims": dims, "layers": L,
                    "loss": "softmax_ce" if w.loss_kind == 0 else "sigmoid_bce",
                    "edges_per_step": edges_per_step, "setup_s": round(t_setup, 1),
-                   "input_aggregate_cached": not args.no_input_cache},
+                   "input_aggregate_cached": not args.no_input_cache,
+                   "layer": "gcn" if kind == 0 else "graphsage-mean"},
         "roofline": roof,
         "phases_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
         "kernel_classes": classes,

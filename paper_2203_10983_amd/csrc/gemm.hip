@@ -102,7 +102,7 @@ __device__ __forceinline__ void store_ncontig(const FragN<COLS> &f, float *__res
 // 3 = add to C, 4 = add to C then ReLU.
 // m_dev (nullable): the row count lives on the device (*m_dev <= M); tiles past it do nothing.
 template <int BN, bool A_KCONTIG, bool B_KCONTIG, int EPI>
-__global__ void __launch_bounds__(kGemmThreads)
+__global__ void __launch_bounds__(kGemmThreads, 4)
 gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const float *__restrict__ B,
             int ldb, float *__restrict__ C, int ldc, int k_chunk, bool vec_a, bool vec_b,
             const float *__restrict__ mask_src, const int *__restrict__ m_dev) {
