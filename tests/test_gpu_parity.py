@@ -282,3 +282,38 @@ def test_train_step_with_cached_input_aggregate(case):
         assert_close(A1.cpu().numpy(), ref["A"][1], "A[1] (other pointer, uncached)")
     finally:
         c.ctx.cache_input_aggregate(None)
+
+
+@pytest.mark.parametrize("kind", [0, 1], ids=["gcn", "sage"])
+def test_sgd_trajectory_on_tiny(kind):
+    """Algorithm 1, update step: three epochs of w <- w - lr * g with a fresh sample per epoch.
+    The HIP library and the oracle each follow their own trajectory from the same start."""
+    import torch
+    import paper_2203_10983_amd as pkg
+    from bns_inputs.workloads import sage_weights
+    w = make_workload(1)
+    if kind == 1:
+        w.W = sage_weights(5, w.dims)
+    dev = torch.device("cuda:0")
+    ctx = pkg.Context(w.part, w.dims, w.loss_kind, device=dev, layer_kind=kind)
+    X = torch.from_numpy(w.X).to(dev)
+    halo_h = [torch.from_numpy(h).to(dev) for h in w.halo_h]
+    labels = torch.from_numpy(w.labels).to(dev)
+    W = [torch.from_numpy(x.copy()).to(dev) for x in w.W]
+    dW = [torch.empty_like(x) for x in W]
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    W_ref = [x.astype(np.float64) for x in w.W]
+    lr, p = 2e-3, 0.5
+    losses = []
+    for epoch in range(3):
+        ctx.train_step(SAMPLING_SEED, epoch, p, X, halo_h, labels, W, dW, None, loss, lr)
+        torch.cuda.synchronize()
+        ref = orc.step(w.part, w.loss_kind, w.X, w.halo_h, w.labels, W_ref, SAMPLING_SEED, epoch, p, lr=lr,
+                       layer_kind=kind)
+        W_ref = ref["W_new"]
+        losses.append(float(loss[0]))
+        assert abs(losses[-1] - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+        for a, b in zip(W, W_ref):
+            assert_close(a.cpu().numpy(), b, f"weights after epoch {epoch}")
+    assert losses[2] < losses[0]
+    ctx.close()
