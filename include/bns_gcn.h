@@ -72,8 +72,11 @@ typedef struct {
 typedef struct {
   int32_t n_layers;     /* L >= 1                                                          */
   const int32_t *dims;  /* host int32[L+1]: d_0 .. d_L (layer l maps d_{l-1} -> d_l)       */
-  int32_t loss_kind;    /* 0: softmax cross-entropy, labels dev int32[n_in]
-                           1: sigmoid binary cross-entropy, labels dev uint8[n_in*d_L]     */
+  int32_t loss_kind;    /* 0: softmax cross-entropy, labels dev int32[n_in] in [0, d_L); a
+                              negative label marks a node outside the training set (the
+                              splits of Table 2): no loss term, zero gradient
+                           1: sigmoid binary cross-entropy, labels dev uint8[n_in*d_L] in
+                              {0, 1}; the value 255 marks an entry outside the training set  */
   int32_t layer_kind;   /* 0: GCN layer of Appendix A, H' = sigma(P H W), W f32[d_in*d_out]
                            1: GraphSAGE with a mean aggregator (Section 2),
                               H' = sigma([mean of neighbours | H] W), W f32[2*d_in*d_out] with
@@ -155,6 +158,13 @@ bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
                           const float *const *halo_h, const void *labels, float *const *W,
                           float *const *dW, float *const *dhalo, float *loss, float lr,
                           void *stream);
+
+/* Adam, the optimiser of the paper's experiments (Section 4; Kingma & Ba 2015), as an alternative
+ * to the plain update of Algorithm 1: call bns_train_step with lr = 0, then this once per weight
+ * matrix.  m, v: dev f32[n] moment buffers owned by the caller (zero before the first step);
+ * t >= 1 is the step count (bias correction).  Needs no context. */
+bns_status bns_adam_update(float *W, const float *dW, float *m, float *v, int64_t n, float lr,
+                           float beta1, float beta2, float eps, int32_t t, void *stream);
 
 /* Static-inner caching.  The input features X and the inner-inner edges are the same in every
  * epoch; sampling only changes the boundary entries of a row (Appendix D).  This call aggregates the

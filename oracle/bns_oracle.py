@@ -184,21 +184,37 @@ def loss_and_grad(logits, labels, loss_kind):
     cross-entropy summed over labels, labels {0,1}[n, C].
     """
     z = np.asarray(logits, dtype=np.float64)
+    labels = np.asarray(labels)
     if loss_kind == 0:
+        train = labels >= 0                      # a negative label: node outside the training set
         m = z.max(axis=1, keepdims=True)
         e = np.exp(z - m)
         se = e.sum(axis=1, keepdims=True)
         lse = (m + np.log(se))[:, 0]
         idx = np.arange(z.shape[0])
-        loss = float(np.sum(lse - z[idx, labels]))
+        safe = np.where(train, labels, 0)
+        loss = float(np.sum((lse - z[idx, safe])[train]))
         g = e / se
-        g[idx, labels] -= 1.0
+        g[idx, safe] -= 1.0
+        g[~train] = 0.0
         return loss, g
-    y = np.asarray(labels, dtype=np.float64)
-    loss = float(np.sum(np.maximum(z, 0.0) - z * y + np.log1p(np.exp(-np.abs(z)))))
+    train = labels != 255                        # 255: entry outside the training set
+    y = np.where(train, labels, 0).astype(np.float64)
+    terms = np.maximum(z, 0.0) - z * y + np.log1p(np.exp(-np.abs(z)))
+    loss = float(np.sum(terms[train]))
     e = np.exp(-np.abs(z))
     g = np.where(z >= 0, 1.0 / (1.0 + e), e / (1.0 + e)) - y
+    g[~train] = 0.0
     return loss, g
+
+
+def adam_step(W, g, m, v, lr, beta1, beta2, eps, t):
+    """One Adam step (Kingma & Ba 2015, the optimiser of Section 4) -> (W, m, v), fp64."""
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** t)
+    v_hat = v / (1.0 - beta2 ** t)
+    return W - lr * m_hat / (np.sqrt(v_hat) + eps), m, v
 
 
 def backward(part, sub, A, H, W, dZ_last, p):

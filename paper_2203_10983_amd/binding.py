@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libbns_gcn.so")
 
 EXPORTED = ["bns_workspace_bytes", "bns_create", "bns_destroy", "bns_last_error",
             "bns_sample_boundary", "bns_build_sampled_csr", "bns_gcn_layer_fwd",
-            "bns_gcn_layer_bwd", "bns_train_step", "bns_cache_input_aggregate", "bns_ws_view",
+            "bns_gcn_layer_bwd", "bns_train_step", "bns_adam_update", "bns_cache_input_aggregate", "bns_ws_view",
             "bns_profile_enable", "bns_profile_read"]
 
 PHASES = ["sample", "build", "gather", "spmm_fwd", "gemm_fwd", "loss", "gemm_dw", "gemm_da",
@@ -82,6 +82,8 @@ def load_library():
     L.bns_train_step.restype = i32
     L.bns_train_step.argtypes = [vp, u64, u32, f64, vp, C.POINTER(vp), vp, C.POINTER(vp),
                                  C.POINTER(vp), C.POINTER(vp), vp, C.c_float, vp]
+    L.bns_adam_update.restype = i32
+    L.bns_adam_update.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_float, C.c_float, C.c_float, C.c_float, i32, vp]
     L.bns_cache_input_aggregate.restype = i32
     L.bns_cache_input_aggregate.argtypes = [vp, vp, vp]
     L.bns_ws_view.restype = i32
@@ -107,6 +109,14 @@ def _ptr_array(tensors):
     for i, t in enumerate(tensors):
         arr[i] = None if t is None else t.data_ptr()
     return arr
+
+
+def adam_update(W, dW, m, v, lr, beta1=0.9, beta2=0.999, eps=1e-8, t=1):
+    """bns_adam_update on one weight tensor (in place)."""
+    st = load_library().bns_adam_update(_ptr(W), _ptr(dW), _ptr(m), _ptr(v), W.numel(), lr, beta1, beta2,
+                                        eps, t, _stream())
+    if st != 0:
+        raise BnsError(st, "bns_adam_update")
 
 
 class Context:

@@ -480,6 +480,15 @@ bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
   return BNS_OK;
 }
 
+bns_status bns_adam_update(float *W, const float *dW, float *m, float *v, int64_t n, float lr, float beta1,
+                           float beta2, float eps, int32_t t, void *stream) {
+  if (!W || !dW || !m || !v || n < 0 || t < 1) return BNS_EINVAL;
+  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps > 0.f)) return BNS_EINVAL;
+  return adam_update(n, W, dW, m, v, lr, beta1, beta2, eps, t, static_cast<hipStream_t>(stream)) == hipSuccess
+             ? BNS_OK
+             : BNS_EHIP;
+}
+
 bns_status bns_cache_input_aggregate(bns_ctx *ctx, const float *X, void *stream) {
   if (!ctx) return BNS_EINVAL;
   ctx->cache_X = nullptr;

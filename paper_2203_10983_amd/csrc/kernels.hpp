@@ -128,6 +128,9 @@ hipError_t loss_sigmoid_bce(int32_t n, int32_t C, const float *logits, const uin
                             float *dZ, float *partials, float *loss, hipStream_t s);
 // out = dH where H > 0 else 0
 hipError_t relu_mask(int64_t n, const float *dH, const float *H, float *out, hipStream_t s);
+// Adam step t (1-based) on n weights; m, v are the caller's moment buffers.
+hipError_t adam_update(int64_t n, float *W, const float *dW, float *m, float *v, float lr, float b1,
+                       float b2, float eps, int32_t t, hipStream_t s);
 // W -= lr * dW  (Algorithm 1, update step)
 hipError_t sgd_update(int64_t n, float *W, const float *dW, float lr, hipStream_t s);
 

@@ -2,6 +2,8 @@
 // the backward pass and the SGD update (Algorithm 1, update step).  The loss is reduced in a
 // fixed order (per wavefront, per block, then one block over the block partials): two runs give
 // the same bits.
+#include <cmath>
+
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -49,6 +51,10 @@ softmax_ce_kernel(int n, int C, const float *__restrict__ logits, const int32_t 
     const float *z = logits + (size_t)v * C;
     float *g = dZ + (size_t)v * C;
     const int y = labels[v];
+    if (y < 0) {  // node outside the training set: no loss, zero gradient
+      for (int c = lane; c < C; c += kWave) g[c] = 0.f;
+      continue;
+    }
     if (C <= 4 * kWave) {
       float x[4];
       float m = -INFINITY;
@@ -98,6 +104,10 @@ sigmoid_bce_kernel(int64_t total, const float *__restrict__ logits, const uint8_
   float acc = 0.f;
   for (int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x; i < total; i += stride) {
     const float z = logits[i];
+    if (labels[i] == 255) {  // entry outside the training set
+      dZ[i] = 0.f;
+      continue;
+    }
     const float y = (float)labels[i];
     const float e = expf(-fabsf(z));
     acc += fmaxf(z, 0.f) - z * y + log1pf(e);
@@ -142,6 +152,30 @@ __global__ void __launch_bounds__(kT)
 sgd_kernel(int64_t n, float *__restrict__ W, const float *__restrict__ dW, float lr) {
   const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (i < n) W[i] -= lr * dW[i];
+}
+
+// Adam (Kingma & Ba, 2015): m <- b1 m + (1-b1) g, v <- b2 v + (1-b2) g^2,
+// w <- w - lr * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps)
+__global__ void __launch_bounds__(kT)
+adam_kernel(int64_t n, float *__restrict__ W, const float *__restrict__ dW, float *__restrict__ m,
+            float *__restrict__ v, float lr, float b1, float b2, float eps, float c1, float c2) {
+  const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
+  if (i >= n) return;
+  const float g = dW[i];
+  const float mi = b1 * m[i] + (1.f - b1) * g;
+  const float vi = b2 * v[i] + (1.f - b2) * g * g;
+  m[i] = mi;
+  v[i] = vi;
+  W[i] -= lr * (mi * c1) / (sqrtf(vi * c2) + eps);
+}
+
+hipError_t adam_update(int64_t n, float *W, const float *dW, float *m, float *v, float lr, float b1,
+                       float b2, float eps, int32_t t, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const float c1 = (float)(1.0 / (1.0 - pow((double)b1, (double)t)));
+  const float c2 = (float)(1.0 / (1.0 - pow((double)b2, (double)t)));
+  adam_kernel<<<(unsigned)((n + kT - 1) / kT), kT, 0, s>>>(n, W, dW, m, v, lr, b1, b2, eps, c1, c2);
+  return hipGetLastError();
 }
 
 hipError_t sgd_update(int64_t n, float *W, const float *dW, float lr, hipStream_t s) {

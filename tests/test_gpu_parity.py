@@ -317,3 +317,46 @@ def test_sgd_trajectory_on_tiny(kind):
             assert_close(a.cpu().numpy(), b, f"weights after epoch {epoch}")
     assert losses[2] < losses[0]
     ctx.close()
+
+
+@pytest.mark.parametrize("loss_cfg", [1, "bce"], ids=["ce", "bce"])
+def test_training_mask_and_adam(loss_cfg):
+    """Nodes (entries) outside the training set carry no loss and no gradient; Adam follows the
+    oracle's fp64 trajectory for four steps."""
+    import torch
+    import paper_2203_10983_amd as pkg
+    w = make_workload(1) if loss_cfg == 1 else make_workload(4, scale=64)
+    rng = np.random.default_rng(3)
+    if w.loss_kind == 0:
+        w.labels = np.where(rng.random(w.part.n_in) < 0.6, w.labels, -1).astype(np.int32)
+    else:
+        w.labels = np.where(rng.random(w.labels.shape) < 0.6, w.labels, 255).astype(np.uint8)
+    dev = torch.device("cuda:0")
+    ctx = pkg.Context(w.part, w.dims, w.loss_kind, device=dev)
+    X = torch.from_numpy(w.X).to(dev)
+    halo_h = [torch.from_numpy(h).to(dev) for h in w.halo_h]
+    labels = torch.from_numpy(w.labels).to(dev)
+    W = [torch.from_numpy(x.copy()).to(dev) for x in w.W]
+    dW = [torch.empty_like(x) for x in W]
+    m = [torch.zeros_like(x) for x in W]
+    v = [torch.zeros_like(x) for x in W]
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    W_ref = [x.astype(np.float64) for x in w.W]
+    m_ref = [np.zeros_like(x) for x in W_ref]
+    v_ref = [np.zeros_like(x) for x in W_ref]
+    # eps is taken large enough that a gradient element whose sign is decided by rounding moves its
+    # weight by far less than the tolerance (Adam's step is g / (|g| + eps) at t = 1)
+    lr, p, eps = 1e-3, 0.5, 1e-2
+    for t in range(1, 5):
+        ctx.train_step(SAMPLING_SEED, t, p, X, halo_h, labels, W, dW, None, loss, 0.0)
+        for l in range(len(W)):
+            pkg.adam_update(W[l], dW[l], m[l], v[l], lr, eps=eps, t=t)
+        torch.cuda.synchronize()
+        ref = orc.step(w.part, w.loss_kind, w.X, w.halo_h, w.labels, W_ref, SAMPLING_SEED, t, p)
+        assert abs(float(loss[0]) - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+        for l in range(len(W)):
+            assert_close(dW[l].cpu().numpy(), ref["dW"][l], f"dW[{l}] step {t}")
+            W_ref[l], m_ref[l], v_ref[l] = orc.adam_step(W_ref[l], ref["dW"][l], m_ref[l], v_ref[l], lr, 0.9,
+                                                         0.999, eps, t)
+            assert_close(W[l].cpu().numpy(), W_ref[l], f"W[{l}] after Adam step {t}")
+    ctx.close()
