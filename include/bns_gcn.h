@@ -159,6 +159,20 @@ bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
                           float *const *dW, float *const *dhalo, float *loss, float lr,
                           void *stream);
 
+/* The epoch loop of Algorithm 1 as a HIP graph.  bns_graph_capture records one bns_train_step (same
+ * arguments) on `stream`, which must be a created stream, not the null stream; inside the graph
+ * the epoch index lives in device memory, starts at first_epoch and is advanced by one at the end
+ * of every replay, so each replay draws a fresh boundary sample.  bns_graph_replay launches the
+ * recorded step n_epochs times on `stream` without synchronising.  Every pointer passed at capture
+ * time (and the arrays they name) must stay valid and in place until the graph is replaced by a
+ * new capture or the context is destroyed.  With lr > 0 the weights are updated in place, i.e.
+ * n replays run n epochs of Algorithm 1.  Event brackets (bns_profile_enable) are not recorded. */
+bns_status bns_graph_capture(bns_ctx *ctx, uint64_t seed, uint32_t first_epoch, double p, const float *X,
+                             const float *const *halo_h, const void *labels, float *const *W,
+                             float *const *dW, float *const *dhalo, float *loss, float lr,
+                             void *stream);
+bns_status bns_graph_replay(bns_ctx *ctx, int32_t n_epochs, void *stream);
+
 /* Adam, the optimiser of the paper's experiments (Section 4; Kingma & Ba 2015), as an alternative
  * to the plain update of Algorithm 1: call bns_train_step with lr = 0, then this once per weight
  * matrix.  m, v: dev f32[n] moment buffers owned by the caller (zero before the first step);

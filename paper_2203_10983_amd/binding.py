@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libbns_gcn.so")
 
 EXPORTED = ["bns_workspace_bytes", "bns_create", "bns_destroy", "bns_last_error",
             "bns_sample_boundary", "bns_build_sampled_csr", "bns_gcn_layer_fwd",
-            "bns_gcn_layer_bwd", "bns_train_step", "bns_adam_update", "bns_cache_input_aggregate", "bns_ws_view",
+            "bns_gcn_layer_bwd", "bns_train_step", "bns_graph_capture", "bns_graph_replay", "bns_adam_update", "bns_cache_input_aggregate", "bns_ws_view",
             "bns_profile_enable", "bns_profile_read"]
 
 PHASES = ["sample", "build", "gather", "spmm_fwd", "gemm_fwd", "loss", "gemm_dw", "gemm_da",
@@ -82,6 +82,10 @@ def load_library():
     L.bns_train_step.restype = i32
     L.bns_train_step.argtypes = [vp, u64, u32, f64, vp, C.POINTER(vp), vp, C.POINTER(vp),
                                  C.POINTER(vp), C.POINTER(vp), vp, C.c_float, vp]
+    L.bns_graph_capture.restype = i32
+    L.bns_graph_capture.argtypes = L.bns_train_step.argtypes
+    L.bns_graph_replay.restype = i32
+    L.bns_graph_replay.argtypes = [vp, i32, vp]
     L.bns_adam_update.restype = i32
     L.bns_adam_update.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_float, C.c_float, C.c_float, C.c_float, i32, vp]
     L.bns_cache_input_aggregate.restype = i32
@@ -193,6 +197,15 @@ class Context:
         self._check(self._lib.bns_train_step(
             self._ctx, seed, epoch, p, _ptr(X), _ptr_array(halo_h), _ptr(labels), _ptr_array(W),
             _ptr_array(dW), None if dhalo is None else _ptr_array(dhalo), _ptr(loss), lr, _stream()))
+
+    def graph_capture(self, seed, first_epoch, p, X, halo_h, labels, W, dW, dhalo, loss, lr=0.0):
+        """Records one train_step on the CURRENT torch stream (must not be the default stream)."""
+        self._check(self._lib.bns_graph_capture(
+            self._ctx, seed, first_epoch, p, _ptr(X), _ptr_array(halo_h), _ptr(labels), _ptr_array(W),
+            _ptr_array(dW), None if dhalo is None else _ptr_array(dhalo), _ptr(loss), lr, _stream()))
+
+    def graph_replay(self, n_epochs):
+        self._check(self._lib.bns_graph_replay(self._ctx, n_epochs, _stream()))
 
     def cache_input_aggregate(self, X):
         self._check(self._lib.bns_cache_input_aggregate(self._ctx, _ptr(X), _stream()))

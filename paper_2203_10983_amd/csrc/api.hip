@@ -76,6 +76,7 @@ struct bns_ctx {
   const int32_t *cur_row_ptr = nullptr, *cur_col_idx = nullptr, *cur_t_row_ptr = nullptr,
                 *cur_t_col_idx = nullptr;
   const float *cache_X = nullptr;  // features whose inner aggregate sits in ws.C0 (nullptr: none)
+  hipGraphExec_t graph_exec = nullptr;  // captured training step (bns_graph_capture)
   std::string err;
 };
 
@@ -295,12 +296,12 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
   return BNS_OK;
 }
 
-bns_status sample_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p, int32_t *kept_ids,
-                       int32_t *remap, int32_t *n_kept, hipStream_t s) {
+bns_status sample_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, const uint32_t *epoch_dev, double p,
+                       int32_t *kept_ids, int32_t *remap, int32_t *n_kept, hipStream_t s) {
   const uint64_t threshold = (uint64_t)std::floor(p * 4294967296.0);
   PhaseTimer t(ctx, BNS_PHASE_SAMPLE, s);
   BNS_TRY("sample_boundary",
-          sample_boundary(ctx->part.halo_gid, ctx->part.n_halo, seed, epoch, (uint32_t)ctx->part.part_id,
+          sample_boundary(ctx->part.halo_gid, ctx->part.n_halo, seed, epoch, epoch_dev, (uint32_t)ctx->part.part_id,
                           threshold, ctx->ws.ballots, ctx->ws.tile_sums, kept_ids, remap, n_kept, s));
   ctx->cur_kept = kept_ids;
   ctx->cur_remap = remap;
@@ -371,7 +372,10 @@ bns_status bns_create(bns_ctx **out, const bns_partition_desc *part, const bns_m
   return BNS_OK;
 }
 
-void bns_destroy(bns_ctx *ctx) { delete ctx; }
+void bns_destroy(bns_ctx *ctx) {
+  if (ctx && ctx->graph_exec) (void)hipGraphExecDestroy(ctx->graph_exec);
+  delete ctx;
+}
 
 const char *bns_last_error(const bns_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
@@ -381,7 +385,7 @@ bns_status bns_sample_boundary(bns_ctx *ctx, uint64_t seed, uint32_t epoch, doub
   if (bad_p(p)) return fail(ctx, BNS_EINVAL, "p must lie in [0, 1]");
   if (!n_kept || (ctx->part.n_halo > 0 && (!kept_ids || !remap)))
     return fail(ctx, BNS_EINVAL, "null output pointer");
-  return sample_impl(ctx, seed, epoch, p, kept_ids, remap, n_kept, static_cast<hipStream_t>(stream));
+  return sample_impl(ctx, seed, epoch, nullptr, p, kept_ids, remap, n_kept, static_cast<hipStream_t>(stream));
 }
 
 bns_status bns_build_sampled_csr(bns_ctx *ctx, int32_t *row_ptr, int32_t *col_idx, int32_t *t_row_ptr,
@@ -425,9 +429,10 @@ bns_status bns_gcn_layer_bwd(bns_ctx *ctx, int32_t layer, double p, const float 
   return layer_bwd_impl(ctx, layer, p, dZ, A_saved, H_in, W, dW, dH_in, dhalo, nullptr, s);
 }
 
-bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p, const float *X,
-                          const float *const *halo_h, const void *labels, float *const *W, float *const *dW,
-                          float *const *dhalo, float *loss, float lr, void *stream) {
+static bns_status train_step_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, const uint32_t *epoch_dev, double p,
+                                  const float *X, const float *const *halo_h, const void *labels,
+                                  float *const *W, float *const *dW, float *const *dhalo, float *loss, float lr,
+                                  void *stream) {
   if (!ctx) return BNS_EINVAL;
   if (bad_p(p)) return fail(ctx, BNS_EINVAL, "p must lie in [0, 1]");
   if (!X || !labels || !W || !dW || !loss || (ctx->part.n_halo > 0 && !halo_h))
@@ -438,7 +443,7 @@ bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
   hipStream_t s = static_cast<hipStream_t>(stream);
   Layout &w = ctx->ws;
 
-  bns_status st = sample_impl(ctx, seed, epoch, p, w.kept_ids, w.remap, w.counters, s);
+  bns_status st = sample_impl(ctx, seed, epoch, epoch_dev, p, w.kept_ids, w.remap, w.counters, s);
   if (st != BNS_OK) return st;
   st = build_impl(ctx, w.row_ptr, w.col_idx, w.t_row_ptr, w.t_col_idx, w.counters + 1, s);
   if (st != BNS_OK) return st;
@@ -477,6 +482,46 @@ bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
       BNS_TRY("sgd_update", sgd_update((int64_t)(ctx->layer_kind == 1 ? 2 : 1) * ctx->dims[l] * ctx->dims[l + 1], W[l],
                                        dW[l], lr, s));
   }
+  return BNS_OK;
+}
+
+bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p, const float *X,
+                          const float *const *halo_h, const void *labels, float *const *W, float *const *dW,
+                          float *const *dhalo, float *loss, float lr, void *stream) {
+  return train_step_impl(ctx, seed, epoch, nullptr, p, X, halo_h, labels, W, dW, dhalo, loss, lr, stream);
+}
+
+bns_status bns_graph_capture(bns_ctx *ctx, uint64_t seed, uint32_t first_epoch, double p, const float *X,
+                             const float *const *halo_h, const void *labels, float *const *W, float *const *dW,
+                             float *const *dhalo, float *loss, float lr, void *stream) {
+  if (!ctx) return BNS_EINVAL;
+  if (!stream) return fail(ctx, BNS_EINVAL, "graph capture needs a stream other than the null stream");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (ctx->graph_exec) { (void)hipGraphExecDestroy(ctx->graph_exec); ctx->graph_exec = nullptr; }
+  uint32_t *epoch_dev = reinterpret_cast<uint32_t *>(ctx->ws.counters + 2);
+  BNS_TRY("set_counter", set_counter(epoch_dev, first_epoch, s));
+  const uint32_t saved_mask = ctx->prof.mask;
+  ctx->prof.mask = 0;  // event brackets are not part of the graph
+  BNS_TRY("hipStreamBeginCapture", hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+  bns_status st = train_step_impl(ctx, seed, 0, epoch_dev, p, X, halo_h, labels, W, dW, dhalo, loss, lr, stream);
+  hipError_t e_bump = st == BNS_OK ? bump_counter(epoch_dev, s) : hipSuccess;
+  hipGraph_t graph = nullptr;
+  hipError_t e_end = hipStreamEndCapture(s, &graph);
+  ctx->prof.mask = saved_mask;
+  if (st != BNS_OK) { if (graph) (void)hipGraphDestroy(graph); return st; }
+  if (e_bump != hipSuccess) { if (graph) (void)hipGraphDestroy(graph); return hip_fail(ctx, "bump_counter", e_bump); }
+  if (e_end != hipSuccess) return hip_fail(ctx, "hipStreamEndCapture", e_end);
+  hipError_t e_inst = hipGraphInstantiate(&ctx->graph_exec, graph, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(graph);
+  if (e_inst != hipSuccess) { ctx->graph_exec = nullptr; return hip_fail(ctx, "hipGraphInstantiate", e_inst); }
+  return BNS_OK;
+}
+
+bns_status bns_graph_replay(bns_ctx *ctx, int32_t n_epochs, void *stream) {
+  if (!ctx || n_epochs < 0) return BNS_EINVAL;
+  if (!ctx->graph_exec) return fail(ctx, BNS_EINVAL, "bns_graph_capture has not been called");
+  for (int i = 0; i < n_epochs; ++i)
+    BNS_TRY("hipGraphLaunch", hipGraphLaunch(ctx->graph_exec, static_cast<hipStream_t>(stream)));
   return BNS_OK;
 }
 

@@ -214,17 +214,32 @@ kept_rows_fill_kernel(const int32_t *__restrict__ n_kept, const int32_t *__restr
   for (int i = sub; i < len; i += 8) t_col_idx[dst + i] = halo_col[src + i];
 }
 
+__global__ void __launch_bounds__(kThreads)
+copy_static_kernel(const int32_t *__restrict__ a_src, int64_t a_n, int32_t *__restrict__ a_dst,
+                   const int32_t *__restrict__ b_src, int64_t b_n, int32_t *__restrict__ b_dst) {
+  const int64_t stride = (int64_t)gridDim.x * kThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < a_n + b_n; i += stride) {
+    if (i < a_n) a_dst[i] = a_src[i];
+    else b_dst[i - a_n] = b_src[i - a_n];
+  }
+}
+
 hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
                                 const int32_t *t_in_ptr, const int32_t *t_in_col,
                                 const int32_t *halo_ptr, const int32_t *halo_col,
                                 const int32_t *kept_ids, const int32_t *n_kept, int32_t *hlen,
                                 int32_t *tile_sums, int32_t *t_row_ptr, int32_t *t_col_idx,
                                 hipStream_t s) {
-  // rows of inner nodes never change: the transpose of the inner-inner block
-  hipError_t e = hipMemcpyAsync(t_row_ptr, t_in_ptr, sizeof(int32_t) * ((size_t)n_in + 1),
-                                hipMemcpyDeviceToDevice, s);
-  if (e != hipSuccess) return e;
-  e = hipMemcpyAsync(t_col_idx, t_in_col, sizeof(int32_t) * (size_t)e_in, hipMemcpyDeviceToDevice, s);
+  // rows of inner nodes never change: the transpose of the inner-inner block (copied by a kernel,
+  // so that the whole step stays a plain chain of kernel nodes under graph capture)
+  {
+    const int64_t n4 = ((int64_t)n_in + 1 + e_in + 3) / 4;
+    int64_t blocks = (n4 + kThreads - 1) / kThreads;
+    if (blocks > 16384) blocks = 16384;
+    copy_static_kernel<<<(unsigned)blocks, kThreads, 0, s>>>(t_in_ptr, (int64_t)n_in + 1, t_row_ptr, t_in_col,
+                                                            e_in, t_col_idx);
+  }
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (n_halo == 0) return hipSuccess;
   // rows of kept boundary nodes: their static lists of inner neighbours, in kept order

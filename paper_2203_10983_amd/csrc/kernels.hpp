@@ -22,8 +22,9 @@ hipError_t scan_sums_inplace(int32_t *sums, int nb, int32_t *total_out, hipStrea
 
 // ---- sample.hip (Algorithm 1, selection step) -------------------------------------------------
 // ballots: scratch uint64[ceil(B/64)]; tile_sums: scratch int32[scan_tiles(B)+1].
+// epoch_dev (nullable): the epoch index is read from device memory instead of `epoch`.
 hipError_t sample_boundary(const int64_t *halo_gid, int32_t n_halo, uint64_t seed, uint32_t epoch,
-                           uint32_t part_id, uint64_t threshold, uint64_t *ballots,
+                           const uint32_t *epoch_dev, uint32_t part_id, uint64_t threshold, uint64_t *ballots,
                            int32_t *tile_sums, int32_t *kept_ids, int32_t *remap, int32_t *n_kept,
                            hipStream_t s);
 
@@ -131,6 +132,9 @@ hipError_t relu_mask(int64_t n, const float *dH, const float *H, float *out, hip
 // Adam step t (1-based) on n weights; m, v are the caller's moment buffers.
 hipError_t adam_update(int64_t n, float *W, const float *dW, float *m, float *v, float lr, float b1,
                        float b2, float eps, int32_t t, hipStream_t s);
+// *counter = value / *counter += 1 (one thread; the device-side epoch index of graph replay)
+hipError_t set_counter(uint32_t *counter, uint32_t value, hipStream_t s);
+hipError_t bump_counter(uint32_t *counter, hipStream_t s);
 // W -= lr * dW  (Algorithm 1, update step)
 hipError_t sgd_update(int64_t n, float *W, const float *dW, float lr, hipStream_t s);
 

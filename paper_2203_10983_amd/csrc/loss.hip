@@ -178,6 +178,18 @@ hipError_t adam_update(int64_t n, float *W, const float *dW, float *m, float *v,
   return hipGetLastError();
 }
 
+__global__ void counter_kernel(uint32_t *counter, uint32_t value, bool bump) {
+  *counter = bump ? *counter + 1u : value;
+}
+hipError_t set_counter(uint32_t *counter, uint32_t value, hipStream_t s) {
+  counter_kernel<<<1, 1, 0, s>>>(counter, value, false);
+  return hipGetLastError();
+}
+hipError_t bump_counter(uint32_t *counter, hipStream_t s) {
+  counter_kernel<<<1, 1, 0, s>>>(counter, 0u, true);
+  return hipGetLastError();
+}
+
 hipError_t sgd_update(int64_t n, float *W, const float *dW, float lr, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   sgd_kernel<<<(unsigned)((n + kT - 1) / kT), kT, 0, s>>>(n, W, dW, lr);

@@ -32,8 +32,9 @@ constexpr int kWordsPerTile = kScanTile / kWave;          // 32
 // number of kept nodes per tile.
 __global__ void __launch_bounds__(kSampleThreads)
 sample_flags_kernel(const int64_t *__restrict__ halo_gid, int32_t n_halo, uint32_t k0, uint32_t k1,
-                    uint32_t epoch, uint32_t part_id, uint64_t threshold,
-                    uint64_t *__restrict__ ballots, int32_t *__restrict__ tile_sums) {
+                    uint32_t epoch, const uint32_t *__restrict__ epoch_dev, uint32_t part_id,
+                    uint64_t threshold, uint64_t *__restrict__ ballots, int32_t *__restrict__ tile_sums) {
+  if (epoch_dev) epoch = *epoch_dev;  // epoch counter kept on the device (graph replay)
   const int lane = lane_id();
   int cnt = 0;
 #pragma unroll
@@ -91,12 +92,12 @@ sample_write_kernel(int32_t n_halo, const uint64_t *__restrict__ ballots,
 }
 
 hipError_t sample_boundary(const int64_t *halo_gid, int32_t n_halo, uint64_t seed, uint32_t epoch,
-                           uint32_t part_id, uint64_t threshold, uint64_t *ballots,
+                           const uint32_t *epoch_dev, uint32_t part_id, uint64_t threshold, uint64_t *ballots,
                            int32_t *tile_sums, int32_t *kept_ids, int32_t *remap, int32_t *n_kept,
                            hipStream_t s) {
   const int nb = scan_tiles(n_halo) > 0 ? scan_tiles(n_halo) : 1;
   sample_flags_kernel<<<nb, kSampleThreads, 0, s>>>(halo_gid, n_halo, (uint32_t)seed,
-                                                    (uint32_t)(seed >> 32), epoch, part_id,
+                                                    (uint32_t)(seed >> 32), epoch, epoch_dev, part_id,
                                                     threshold, ballots, tile_sums);
   (void)scan_sums_inplace(tile_sums, nb, n_kept, s);
   if (n_halo > 0)

@@ -360,3 +360,79 @@ def test_training_mask_and_adam(loss_cfg):
                                                          0.999, eps, t)
             assert_close(W[l].cpu().numpy(), W_ref[l], f"W[{l}] after Adam step {t}")
     ctx.close()
+
+
+@pytest.mark.parametrize("cfg,scale,kind,cached", [(1, 1, 0, False), (3, 16, 0, True), (3, 16, 1, False)],
+                         ids=["tiny-gcn", "cfg3s16-gcn-cached", "cfg3s16-sage"])
+def test_graph_replay_equals_eager_epochs(cfg, scale, kind, cached):
+    """Algorithm 1's epoch loop recorded once as a HIP graph: every replay (fresh sample from the
+    device-side epoch index, in-place SGD) must give bit for bit what the eager entry point gives
+    for that epoch.  Eager torch work and synchronisations sit between the replays."""
+    import torch
+    import paper_2203_10983_amd as pkg
+    from bns_inputs.workloads import sage_weights
+    w = make_workload(cfg, scale=scale)
+    if kind == 1:
+        w.W = sage_weights(5, w.dims)
+    dev = torch.device("cuda:0")
+    ctx = pkg.Context(w.part, w.dims, w.loss_kind, device=dev, layer_kind=kind)
+    X = torch.from_numpy(w.X).to(dev)
+    halo_h = [torch.from_numpy(h).to(dev) for h in w.halo_h]
+    labels = torch.from_numpy(w.labels).to(dev)
+    L = w.n_layers
+    lr, p, first, n_ep = 1e-4, 0.25, 3, 4
+
+    def fresh():
+        W = [torch.from_numpy(x.copy()).to(dev) for x in w.W]
+        dW = [torch.zeros_like(x) for x in W]
+        dhalo = [torch.zeros((w.part.n_halo, w.dims[l]), dtype=torch.float32, device=dev) for l in range(L)]
+        return W, dW, dhalo, torch.zeros(1, dtype=torch.float32, device=dev)
+
+    if cached:
+        ctx.cache_input_aggregate(X)
+    # eager trajectory
+    W, dW, dhalo, loss = fresh()
+    want = []
+    for e in range(n_ep):
+        ctx.train_step(SAMPLING_SEED, first + e, p, X, halo_h, labels, W, dW, dhalo, loss, lr)
+        torch.cuda.synchronize()
+        nk = int(ctx.ws_tensor(pkg.VIEW_N_KEPT)[0])
+        want.append(dict(loss=loss.clone(), W=[x.clone() for x in W], dW=[x.clone() for x in dW],
+                         dhalo=[x[:nk].clone() for x in dhalo[1:]], nk=nk))
+    assert len({x["nk"] for x in want}) > 1 or w.part.n_halo < 8, "epochs should draw different samples"
+    # graph trajectory
+    W, dW, dhalo, loss = fresh()
+    side = torch.cuda.Stream(device=dev)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ctx.graph_capture(SAMPLING_SEED, first, p, X, halo_h, labels, W, dW, dhalo, loss, lr)
+    side.synchronize()
+    for a, b in zip(W, w.W):
+        assert np.array_equal(a.cpu().numpy(), b), "capture must not run the step"
+    for e in range(n_ep):
+        with torch.cuda.stream(side):
+            ctx.graph_replay(1)
+        side.synchronize()
+        _ = float((X[:64] * 2.0).sum())           # eager work between replays
+        torch.cuda.synchronize()
+        nk = int(ctx.ws_tensor(pkg.VIEW_N_KEPT)[0])
+        assert nk == want[e]["nk"]
+        assert torch.equal(loss, want[e]["loss"]), f"loss of replay {e}"
+        for l in range(L):
+            assert torch.equal(W[l], want[e]["W"][l]), f"W[{l}] after replay {e}"
+            assert torch.equal(dW[l], want[e]["dW"][l]), f"dW[{l}] of replay {e}"
+        for l in range(1, L):
+            assert torch.equal(dhalo[l][:nk], want[e]["dhalo"][l - 1]), f"dhalo[{l}] of replay {e}"
+    # several replays in one call continue the same trajectory
+    W2 = [x.clone() for x in W]
+    with torch.cuda.stream(side):
+        ctx.graph_replay(2)
+    side.synchronize()
+    for e in (n_ep, n_ep + 1):
+        ctx.train_step(SAMPLING_SEED, first + e, p, X, halo_h, labels, W2, dW, dhalo, loss, lr)
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert torch.equal(W[l], W2[l])
+    if cached:
+        ctx.cache_input_aggregate(None)
+    ctx.close()
