@@ -364,9 +364,9 @@ bns_status bns_create(bns_ctx **out, const bns_partition_desc *part, const bns_m
   BNS_TRY("degree_rsqrt(halo)", degree_rsqrt(part->deg_halo, part->n_halo, ctx->ws.dis_halo, s));
   BNS_TRY("build_static_split", build_static_split(part->n_in, part->row_ptr0, part->col0, ctx->ws.split,
                                                    ctx->ws.tile_sums, s));
-  BNS_TRY("build_seg_plan(fwd)", build_seg_plan(part->n_in, part->row_ptr0, &ctx->ws.plan_f, ctx->ws.seg_tmp_a,
+  BNS_TRY("build_seg_plan(fwd)", build_seg_plan(part->n_in, part->nnz0, part->row_ptr0, &ctx->ws.plan_f, ctx->ws.seg_tmp_a,
                                                  ctx->ws.seg_tmp_b, ctx->ws.tile_sums, s));
-  BNS_TRY("build_seg_plan(bwd)", build_seg_plan(part->n_in, part->t_in_ptr, &ctx->ws.plan_b, ctx->ws.seg_tmp_a,
+  BNS_TRY("build_seg_plan(bwd)", build_seg_plan(part->n_in, part->e_in, part->t_in_ptr, &ctx->ws.plan_b, ctx->ws.seg_tmp_a,
                                                  ctx->ws.seg_tmp_b, ctx->ws.tile_sums, s));
   BNS_TRY("set-up sync", hipStreamSynchronize(s));
   return BNS_OK;

@@ -66,13 +66,14 @@ struct SegPlan {
   int32_t *part_ptr;  // int32[n_rows+1] first partial-sum slot of each multi-segment row
   int32_t *mrow;      // int32[n_multi]  rows with more than one segment
   int32_t n_seg, n_part, n_multi;  // host copies of the totals
+  int32_t avg_len;                 // entries per row of the static pattern (launch heuristics)
 };
 inline int64_t seg_max_segments(int64_t rows, int64_t nnz) { return rows + nnz / kSegLen + 1; }
 inline int64_t seg_max_parts(int64_t nnz) { return 2 * (nnz / kSegLen) + 2; }
 inline int64_t seg_max_multi(int64_t nnz) { return nnz / kSegLen + 1; }
 // Fills *plan (its arrays must be allocated to the bounds above) and waits for the stream.
-// tmp_a: scratch int32[n_rows], tmp_b: scratch int32[n_rows+1].
-hipError_t build_seg_plan(int32_t n_rows, const int32_t *row_ptr, SegPlan *plan, int32_t *tmp_a,
+// tmp_a: scratch int32[n_rows], tmp_b: scratch int32[n_rows+1].  nnz: entries of the pattern.
+hipError_t build_seg_plan(int32_t n_rows, int64_t nnz, const int32_t *row_ptr, SegPlan *plan, int32_t *tmp_a,
                           int32_t *tmp_b, int32_t *tile_sums, hipStream_t s);
 
 // Hu[r,:] = (s_halo * dis_halo[b]) * halo_h[b,:], b = kept_ids[r], r < *n_kept (dis_halo nullable = 1).

@@ -53,11 +53,16 @@ struct SpmmArgs {
   const int32_t *row_take;     // then use row_take[row] entries instead of the rest (nullable)
   const float *init;           // out0 row = scale * (init row + sum) (nullable)
   bool skip_self;              // entries with column == row contribute nothing (mean aggregator)
+  // feature slicing over the XCDs (n_slices = 1: off).  Workgroups are handed to the 8 XCDs in
+  // turn, so workgroup b runs on XCD b % 8; with n_slices = S that XCD only ever touches the
+  // d_slice = d / S floats of slice (b % 8) % S of every feature row, and its private L2 holds S
+  // times as many distinct rows.
+  int32_t n_slices, d_slice;
 };
 
 // Scale, optional ReLU mask and store of one finished row slice held as acc[c][i].
 template <int VEC, int MAXCH>
-__device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, int nvec,
+__device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, int nvec, int d_off,
                                            float (&acc)[MAXCH][VEC]) {
   using V = typename Vec<VEC>::T;
   const int d = a.d;
@@ -66,15 +71,15 @@ __device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, i
   const float *mask = nullptr;
   const float *init = nullptr;
   if (row < a.n_split) {
-    if (a.init) init = a.init + (size_t)row * d;
+    if (a.init) init = a.init + (size_t)row * d + d_off;
     scale = a.out_scale0 ? a.out_scale0[row] : 1.f;
-    out = a.out0 + (size_t)row * d;
-    if (a.mask_src) mask = a.mask_src + (size_t)row * d;
+    out = a.out0 + (size_t)row * d + d_off;
+    if (a.mask_src) mask = a.mask_src + (size_t)row * d + d_off;
   } else {
     if (a.out1 == nullptr) return;
     const int r = row - a.n_split;
     scale = a.dis_halo ? a.s_halo * a.dis_halo[a.kept_ids[r]] : a.s_halo;
-    out = a.out1 + (size_t)r * d;
+    out = a.out1 + (size_t)r * d + d_off;
   }
 #pragma unroll
   for (int c = 0; c < MAXCH; ++c) {
@@ -111,10 +116,18 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
   const int lane = lane_id();
   const int g = lane / LPR, sl = lane % LPR;
   const int d = a.d;
-  const int nvec = d / VEC;
+  int nvec = d / VEC, d_off = 0;
+  int bid = blockIdx.x, nblk = gridDim.x;
+  if (a.n_slices > 1) {  // gridDim.x is a multiple of 8
+    const int x = bid & 7, per = 8 / a.n_slices;
+    d_off = (x % a.n_slices) * a.d_slice;
+    nvec = a.d_slice / VEC;
+    bid = (bid >> 3) * per + x / a.n_slices;
+    nblk = (nblk >> 3) * per;
+  }
   // work units: the static segments, then one unit per kept boundary row (count on the device)
   const int n_units = a.plan.n_seg + (a.n_extra_dev ? *a.n_extra_dev : 0);
-  for (int unit = blockIdx.x * 4 + (threadIdx.x >> 6); unit < n_units; unit += gridDim.x * 4) {
+  for (int unit = bid * 4 + (threadIdx.x >> 6); unit < n_units; unit += nblk * 4) {
   int row, seg = 0, nseg = 1;
   if (unit < a.plan.n_seg) {
     row = a.plan.seg_row[unit];
@@ -149,11 +162,11 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
     if (lane < cnt) {
       const int c = a.col_idx[base + lane];
       if (c < a.n_split) {
-        p_l = (unsigned long long)(a.src0 + (size_t)c * d);
+        p_l = (unsigned long long)(a.src0 + (size_t)c * d + d_off);
         w_l = a.w_col ? a.w_col[c] : 1.f;
         if (a.skip_self && c == row) w_l = 0.f;  // the stored self-loop is not a neighbour
       } else {
-        p_l = (unsigned long long)(a.src1 + (size_t)(c - a.n_split) * d);
+        p_l = (unsigned long long)(a.src1 + (size_t)(c - a.n_split) * d + d_off);
         w_l = 1.f;
       }
     }
@@ -203,9 +216,9 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
   if (g != 0) {
     // only the first lane group holds the folded sums
   } else if (nseg == 1) {
-    finish_row<VEC, MAXCH>(a, row, sl, nvec, acc);
+    finish_row<VEC, MAXCH>(a, row, sl, nvec, d_off, acc);
   } else {
-    V *part = reinterpret_cast<V *>(a.partials + (size_t)(a.plan.part_ptr[row] + seg) * d);
+    V *part = reinterpret_cast<V *>(a.partials + (size_t)(a.plan.part_ptr[row] + seg) * d + d_off);
 #pragma unroll
     for (int c = 0; c < MAXCH; ++c) {
       const int iv = c * kWave + sl;
@@ -258,25 +271,39 @@ __global__ void __launch_bounds__(256) spmm_combine_kernel(const SpmmArgs a) {
         for (int i = 0; i < VEC; ++i) acc[c][i] += px[i];
       }
   }
-  finish_row<VEC, MAXCH>(a, row, lane, nvec, acc);
+  finish_row<VEC, MAXCH>(a, row, lane, nvec, 0, acc);
 }
 
 template <int VEC>
-static hipError_t launch_spmm_vec(const SpmmArgs &a, int64_t max_units, hipStream_t s) {
-  const int nvec = a.d / VEC;
+static hipError_t launch_spmm_vec(const SpmmArgs &a_in, int64_t max_units, hipStream_t s) {
+  SpmmArgs a = a_in;
+  a.n_slices = 1;
+  a.d_slice = a.d;
+  // Wide rows are cut into slices of 128 floats (64 where rows are long enough to keep a
+  // wavefront busy with a quarter of its lanes per neighbour); measured on the five workloads,
+  // narrower slices lose more to the repeated index walk than the L2 gains.
+  if (VEC == 4) {
+    const int target = a.plan.avg_len >= 64 ? 64 : 128;
+    int S = 1;
+    while (S < 8 && a.d / (2 * S) >= target && a.d % (2 * S * VEC) == 0) S *= 2;
+    a.n_slices = S;
+    a.d_slice = a.d / S;
+  }
+  const int nvec = a.d_slice / VEC;
+  const int full_nvec = a.d / VEC;
   // one wavefront per static segment; the kept boundary rows, whose count lives on the device,
   // are strided over by a bounded number of extra blocks (blocks past the count would only cost
   // dispatch time)
   const int64_t seg_blocks = ((int64_t)a.plan.n_seg + 3) / 4;
   const int64_t extra_blocks = std::min<int64_t>((max_units - a.plan.n_seg + 3) / 4, 8192);
-  const unsigned blocks = (unsigned)(seg_blocks + std::max<int64_t>(extra_blocks, 0));
+  unsigned blocks = (unsigned)(seg_blocks + std::max<int64_t>(extra_blocks, 0));
   const unsigned cblocks = (unsigned)((a.plan.n_multi + 3) / 4);
   if (blocks == 0) return hipSuccess;
-#define BNS_SPMM(MAXCH, LPR)                                                        \
-  do {                                                                              \
-    spmm_kernel<VEC, MAXCH, LPR><<<blocks, 256, 0, s>>>(a);                         \
-    if (cblocks) spmm_combine_kernel<VEC, MAXCH><<<cblocks, 256, 0, s>>>(a);        \
-  } while (0)
+  if (a.n_slices > 1) {
+    const unsigned per = 8 / a.n_slices;
+    blocks = (blocks + per - 1) / per * 8;
+  }
+#define BNS_SPMM(MAXCH, LPR) spmm_kernel<VEC, MAXCH, LPR><<<blocks, 256, 0, s>>>(a)
   if (nvec <= 1) BNS_SPMM(1, 1);
   else if (nvec <= 2) BNS_SPMM(1, 2);
   else if (nvec <= 4) BNS_SPMM(1, 4);
@@ -290,6 +317,15 @@ static hipError_t launch_spmm_vec(const SpmmArgs &a, int64_t max_units, hipStrea
   else if (nvec <= 512) BNS_SPMM(8, 64);
   else return hipErrorInvalidValue;
 #undef BNS_SPMM
+  if (cblocks) {
+#define BNS_COMBINE(MAXCH) spmm_combine_kernel<VEC, MAXCH><<<cblocks, 256, 0, s>>>(a)
+    if (full_nvec <= 64) BNS_COMBINE(1);
+    else if (full_nvec <= 128) BNS_COMBINE(2);
+    else if (full_nvec <= 256) BNS_COMBINE(4);
+    else if (full_nvec <= 384) BNS_COMBINE(6);
+    else BNS_COMBINE(8);
+#undef BNS_COMBINE
+  }
   return hipGetLastError();
 }
 
@@ -360,7 +396,7 @@ seg_fill_kernel(int32_t n_rows, const int32_t *__restrict__ seg_ptr, const int32
   if (s1 - s0 > 1) mrow[mpos[v]] = v;
 }
 
-hipError_t build_seg_plan(int32_t n_rows, const int32_t *row_ptr, SegPlan *plan, int32_t *tmp_a,
+hipError_t build_seg_plan(int32_t n_rows, int64_t nnz, const int32_t *row_ptr, SegPlan *plan, int32_t *tmp_a,
                           int32_t *tmp_b, int32_t *tile_sums, hipStream_t s) {
   const unsigned blocks = (unsigned)((n_rows + 255) / 256);
   seg_count_kernel<<<blocks, 256, 0, s>>>(n_rows, row_ptr, tmp_a);
@@ -388,6 +424,7 @@ hipError_t build_seg_plan(int32_t n_rows, const int32_t *row_ptr, SegPlan *plan,
   plan->n_seg = tot[0];
   plan->n_part = tot[1];
   plan->n_multi = tot[2];
+  plan->avg_len = n_rows > 0 ? (int32_t)(nnz / n_rows) : 0;
   return hipSuccess;
 }
 
