@@ -164,6 +164,24 @@ def main():
     for k, fl in gemm_flops.items():
         classes[k + "_TFLOPs"] = fl / (per_step_ms[k] * 1e-3) / 1e12 if per_step_ms[k] else None
 
+    # ---- whole-step roofline: sum over kernel classes of max(compulsory bytes / HBM peak, flops / MFMA peak)
+    gemm_bytes = {"gemm_fwd": sum(4 * n_in * (kw * dims[l - 1] + dims[l]) for l in range(1, L + 1)),
+                  "gemm_dw": sum(4 * n_in * (kw * dims[l - 1] + dims[l]) for l in range(1, L + 1)),
+                  "gemm_da": sum(4 * n_in * (kw * dims[l - 1] + dims[l]) for l in range(2, L + 1))}
+    t_roof = (fwd_bytes + bwd_bytes) / (HBM_PEAK_GBS * 1e9)
+    t_roof += sum(max(gemm_flops[k] / (FP32_MFMA_PEAK_TFLOPS * 1e12), gemm_bytes[k] / (HBM_PEAK_GBS * 1e9))
+                  for k in gemm_flops)
+    t_roof += sum(8 * n_kept * dims[l - 1] for l in range(1, L + 1)) / (HBM_PEAK_GBS * 1e9)      # halo gather
+    t_roof += 8 * n_in * dims[L] / (HBM_PEAK_GBS * 1e9)                                          # loss
+    t_roof += (12 * P.n_halo + 4 * n_kept + 8 * P.e_bd + 8 * nnz + 8 * (n_in + 1)) / (HBM_PEAK_GBS * 1e9)  # sample + CSRs
+    step_roofline = {"t_roof_ms": t_roof * 1e3, "frac": t_roof * 1e3 / ms_per_step,
+                     "note": "sum over kernel classes of max(compulsory bytes / 8 TB/s, flops / 157.3 TFLOP/s) / ms_per_step"}
+    # activations held for the backward pass per layer (floats), beside the memory model of Eq. 4
+    held = [n_in * dims[l - 1] + n_in * dims[l] + n_kept * dims[l - 1] for l in range(1, L + 1)]
+    eq4 = [(3 * n_in + n_kept) * dims[l] for l in range(1, L + 1)]
+    memory = {"held_floats_per_layer": held, "eq4_floats_per_layer": eq4,
+              "workspace_bytes": ctx.ws_bytes}
+
     # ---- CPU baseline: the oracle as it stands, one full step of the same workload --------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -191,6 +209,8 @@ def main():
         "phases_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
         "kernel_classes": classes,
         "sampling_overhead": (per_step_ms["sample"] + per_step_ms["build"]) / ms_per_step,
+        "step_roofline": step_roofline,
+        "memory": memory,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
