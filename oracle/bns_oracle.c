@@ -79,6 +79,26 @@ int64_t bnso_sample(uint64_t seed, uint32_t epoch, uint32_t part_id, double p,
   return n_kept;
 }
 
+/* Dropout on hidden activations (Section 4 trains with dropout; the element-wise draw is this
+ * build's reading): element (row, col) of the output of hidden layer `layer` is kept with
+ * probability 1 - q.  The draw is word (row mod 4) of Philox-4x32-10 on the counter
+ * (row div 4, col, part_id * 256 + layer, epoch) under the key (seed lo, seed hi xor 0x64726F70),
+ * a stream separate from the boundary draw; keep  <=>  word < floor((1 - q) * 2^32). */
+void bnso_dropout_mask(uint64_t seed, uint32_t epoch, uint32_t part_id, uint32_t layer,
+                       int64_t n_rows, int64_t n_cols, double q, uint8_t *keep) {
+  const uint64_t T = bnso_threshold(1.0 - q);
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32) ^ 0x64726F70u};
+#pragma omp parallel for schedule(static)
+  for (int64_t row = 0; row < n_rows; ++row) {
+    for (int64_t col = 0; col < n_cols; ++col) {
+      uint32_t ctr[4] = {(uint32_t)(row >> 2), (uint32_t)col, (part_id << 8) | layer, epoch};
+      uint32_t out[4];
+      bnso_philox4x32_10(ctr, key, out);
+      keep[row * n_cols + col] = (uint64_t)out[row & 3] < T ? 1 : 0;
+    }
+  }
+}
+
 /* Algorithm 1, subgraph step: node-induced subgraph on V u U.  Inner columns stay,
  * boundary column n_in+b stays iff b in U and becomes n_in+rank(b); order kept. */
 int64_t bnso_induced_csr(int64_t n_in, const int32_t *row_ptr0, const int32_t *col0,

@@ -77,6 +77,8 @@ def lib():
                                           _f64p, _f32p, _f64p]
         L.bnso_aggregate_mean_bwd.argtypes = [C.c_int64, C.c_int64, C.c_int64, _i32p, _i32p, _i32p,
                                               C.c_double, _f64p, _f64p, _f64p]
+        L.bnso_dropout_mask.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int64, C.c_int64,
+                                        C.c_double, np.ctypeslib.ndpointer(np.uint8, flags="C_CONTIGUOUS")]
         _lib = L
     return _lib
 
@@ -159,10 +161,32 @@ def halo_scale(p: float, n_kept: int) -> float:
     return 1.0 / p if n_kept > 0 else 1.0
 
 
-def forward(part, sub, X, halo_h, W, p, Z_out=None):
+def dropout_mask(seed, epoch, part_id, layer, n_rows, n_cols, q):
+    """uint8[n_rows, n_cols]: 1 where the element of hidden layer ``layer`` survives dropout."""
+    keep = np.zeros((n_rows, n_cols), dtype=np.uint8)
+    lib().bnso_dropout_mask(seed, epoch, part_id, layer, n_rows, n_cols, float(q), keep)
+    return keep
+
+
+def dropout_scale(q: float) -> float:
+    """1/(1-q) in fp32, the factor that keeps the expectation of a dropped activation."""
+    return float(np.float32(1.0 / (1.0 - q))) if q > 0.0 else 1.0
+
+
+def _hidden(z, part, l, dropout):
+    """ReLU, then (training with dropout = (q, seed, epoch)) drop and rescale."""
+    h = np.maximum(z, 0.0)
+    if dropout is not None and dropout[0] > 0.0:
+        q, seed, epoch = dropout
+        h = h * dropout_mask(seed, epoch, part.part_id, l, h.shape[0], h.shape[1], q) * dropout_scale(q)
+    return h
+
+
+def forward(part, sub, X, halo_h, W, p, Z_out=None, dropout=None):
     """All layers.  ``sub`` = dict(row_ptr, col_idx, kept_ids).  -> (A list, H list) with
     H[0] = X, H[l] = ReLU(A[l] W[l]) for l < L and H[L] = A[L] W[L] (logits).  If ``Z_out`` is a
-    list, the pre-activations A[l] W[l] are appended to it (index l-1)."""
+    list, the pre-activations A[l] W[l] are appended to it (index l-1).  ``dropout`` =
+    (q, seed, epoch): the hidden activations are dropped element-wise and rescaled by 1/(1-q)."""
     L = len(W)
     s = halo_scale(p, sub["kept_ids"].shape[0])
     H = [np.asarray(X, dtype=np.float64)]
@@ -171,7 +195,7 @@ def forward(part, sub, X, halo_h, W, p, Z_out=None):
         a = aggregate(part, sub["row_ptr"], sub["col_idx"], sub["kept_ids"], s, H[l - 1], halo_h[l - 1])
         z = a @ np.asarray(W[l - 1], dtype=np.float64)
         A.append(a)
-        H.append(np.maximum(z, 0.0) if l < L else z)
+        H.append(_hidden(z, part, l, dropout) if l < L else z)
         if Z_out is not None:
             Z_out.append(z)
     return A, H
@@ -217,8 +241,9 @@ def adam_step(W, g, m, v, lr, beta1, beta2, eps, t):
     return W - lr * m_hat / (np.sqrt(v_hat) + eps), m, v
 
 
-def backward(part, sub, A, H, W, dZ_last, p):
-    """-> (dW list[L], dhalo list[L] (entry 0 is None), dH list: dH[l] = grad wrt H[l], l=1..L-1)."""
+def backward(part, sub, A, H, W, dZ_last, p, drop_scale=1.0):
+    """-> (dW list[L], dhalo list[L] (entry 0 is None), dH list: dH[l] = grad wrt H[l], l=1..L-1).
+    With dropout, H[l] > 0 exactly where the unit is active and kept, and its slope is drop_scale."""
     L = len(W)
     s = halo_scale(p, sub["kept_ids"].shape[0])
     dW = [None] * L
@@ -227,7 +252,7 @@ def backward(part, sub, A, H, W, dZ_last, p):
     dZ = dZ_last
     for l in range(L, 0, -1):
         if l < L:
-            dZ = dH[l] * (H[l] > 0.0)
+            dZ = dH[l] * (H[l] > 0.0) * drop_scale
         dW[l - 1] = A[l].T @ dZ
         if l > 1:
             dA = dZ @ np.asarray(W[l - 1], dtype=np.float64).T
@@ -261,7 +286,7 @@ def aggregate_mean_bwd(part, t_row_ptr, t_col_idx, kept_ids, s_halo, dZ):
     return dH, dhalo[:n_u]
 
 
-def forward_sage(part, sub, X, halo_h, W, p, Z_out=None):
+def forward_sage(part, sub, X, halo_h, W, p, Z_out=None, dropout=None):
     """-> (A list, H list): A[l] = mean aggregate z of layer l, H[l] = ReLU([A[l] | H[l-1]] W[l])
     for l < L, no ReLU on the last layer."""
     L = len(W)
@@ -272,13 +297,13 @@ def forward_sage(part, sub, X, halo_h, W, p, Z_out=None):
         a = aggregate_mean(part, sub["row_ptr"], sub["col_idx"], sub["kept_ids"], s, H[l - 1], halo_h[l - 1])
         z = np.hstack([a, H[l - 1]]) @ np.asarray(W[l - 1], dtype=np.float64)
         A.append(a)
-        H.append(np.maximum(z, 0.0) if l < L else z)
+        H.append(_hidden(z, part, l, dropout) if l < L else z)
         if Z_out is not None:
             Z_out.append(z)
     return A, H
 
 
-def backward_sage(part, sub, A, H, W, dZ_last, p):
+def backward_sage(part, sub, A, H, W, dZ_last, p, drop_scale=1.0):
     L = len(W)
     s = halo_scale(p, sub["kept_ids"].shape[0])
     dW = [None] * L
@@ -287,7 +312,7 @@ def backward_sage(part, sub, A, H, W, dZ_last, p):
     dZ = dZ_last
     for l in range(L, 0, -1):
         if l < L:
-            dZ = dH[l] * (H[l] > 0.0)
+            dZ = dH[l] * (H[l] > 0.0) * drop_scale
         d_in = H[l - 1].shape[1]
         dW[l - 1] = np.hstack([A[l], H[l - 1]]).T @ dZ
         if l > 1:
@@ -306,15 +331,17 @@ def sample_and_build(part, seed, epoch, p):
                 t_row_ptr=t_row_ptr, t_col_idx=t_col_idx)
 
 
-def step(part, loss_kind, X, halo_h, labels, W, seed, epoch, p, lr=0.0, layer_kind=0):
+def step(part, loss_kind, X, halo_h, labels, W, seed, epoch, p, lr=0.0, layer_kind=0, dropout=0.0):
     """One iteration of Algorithm 1 on one partition (no exchange, optional SGD).
-    layer_kind 0: GCN layer of Appendix A; 1: GraphSAGE-mean layer of Section 2."""
+    layer_kind 0: GCN layer of Appendix A; 1: GraphSAGE-mean layer of Section 2.
+    dropout: rate q on the hidden activations (0 = none)."""
     sub = sample_and_build(part, seed, epoch, p)
     Z = []
     fwd, bwd = (forward, backward) if layer_kind == 0 else (forward_sage, backward_sage)
-    A, H = fwd(part, sub, X, halo_h, W, p, Z_out=Z)
+    drop = (dropout, seed, epoch) if dropout > 0.0 else None
+    A, H = fwd(part, sub, X, halo_h, W, p, Z_out=Z, dropout=drop)
     loss, dZ = loss_and_grad(H[-1], labels, loss_kind)
-    dW, dhalo, dH = bwd(part, sub, A, H, W, dZ, p)
+    dW, dhalo, dH = bwd(part, sub, A, H, W, dZ, p, drop_scale=dropout_scale(dropout))
     out = dict(sub=sub, A=A, H=H, Z=[None] + Z, loss=loss, dZ_last=dZ, dW=dW, dhalo=dhalo, dH=dH)
     if lr > 0.0:
         out["W_new"] = [np.asarray(w, dtype=np.float64) - lr * g for w, g in zip(W, dW)]
