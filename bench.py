@@ -32,6 +32,8 @@ def main():
     ap.add_argument("--p", type=float, default=None, help="sampling rate (default: the config's first)")
     ap.add_argument("--model", choices=["gcn", "sage"], default="gcn",
                     help="gcn: the GCN layer of the five configs; sage: GraphSAGE-mean, the paper's own model")
+    ap.add_argument("--dropout", type=float, default=0.0,
+                    help="dropout rate on the hidden activations (the five workloads name none: default 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-input-cache", action="store_true",
                     help="do not install the static inner aggregate of layer 1 (bns_cache_input_aggregate)")
@@ -59,6 +61,7 @@ def main():
     L = w.n_layers
     dev = torch.device("cuda:0")
     ctx = pkg.Context(P, w.dims, w.loss_kind, device=dev, layer_kind=kind)
+    ctx.set_dropout(args.dropout)
     X = torch.from_numpy(w.X).to(dev)
     halo_h = [torch.from_numpy(h).to(dev) for h in w.halo_h]
     labels = torch.from_numpy(w.labels).to(dev)
@@ -187,7 +190,8 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import bns_oracle as orc
         tc = time.perf_counter()
-        ref = orc.step(P, w.loss_kind, w.X, w.halo_h, w.labels, w.W, SAMPLING_SEED, 0, p, layer_kind=kind)
+        ref = orc.step(P, w.loss_kind, w.X, w.halo_h, w.labels, w.W, SAMPLING_SEED, 0, p, layer_kind=kind,
+                       dropout=args.dropout)
         dt = time.perf_counter() - tc
         nnz0 = int(ref["sub"]["col_idx"].size)
         cpu = {"value": nnz0 * (2 * L - 1) / dt, "unit": "edges/s", "cores": orc.num_threads(),
@@ -204,7 +208,7 @@ def main():
                    "loss": "softmax_ce" if w.loss_kind == 0 else "sigmoid_bce",
                    "edges_per_step": edges_per_step, "setup_s": round(t_setup, 1),
                    "input_aggregate_cached": not args.no_input_cache,
-                   "layer": "gcn" if kind == 0 else "graphsage-mean"},
+                   "layer": "gcn" if kind == 0 else "graphsage-mean", "dropout": args.dropout},
         "roofline": roof,
         "phases_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
         "kernel_classes": classes,

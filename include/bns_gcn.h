@@ -173,6 +173,18 @@ bns_status bns_graph_capture(bns_ctx *ctx, uint64_t seed, uint32_t first_epoch, 
                              void *stream);
 bns_status bns_graph_replay(bns_ctx *ctx, int32_t n_epochs, void *stream);
 
+/* Dropout on the hidden activations, as in the training set-up of Section 4 (rates 0.1 - 0.5).
+ * With rate q in (0, 1) every element of the output of a layer that has a ReLU (layers 1..L-1 of
+ * bns_train_step, relu != 0 in bns_gcn_layer_fwd) is zeroed with probability q and multiplied by
+ * 1/(1-q) otherwise, and the backward calls scale the gradient of the surviving elements
+ * accordingly (an element that is zero after dropout passes no gradient).  The draw is counter
+ * based: word (row mod 4) of Philox-4x32-10 on the counter (row div 4, column,
+ * part_id * 256 + layer, epoch) under the key (seed lo, seed hi xor 0x64726F70), with the seed and
+ * epoch of the latest bns_sample_boundary / bns_train_step on this context; kept iff the word is
+ * below floor((1-q) * 2^32).  Boundary features are used as handed in (their owners applied their
+ * own dropout).  q = 0 (the default) switches dropout off; q outside [0, 1) -> BNS_EINVAL. */
+bns_status bns_set_dropout(bns_ctx *ctx, double q);
+
 /* Adam, the optimiser of the paper's experiments (Section 4; Kingma & Ba 2015), as an alternative
  * to the plain update of Algorithm 1: call bns_train_step with lr = 0, then this once per weight
  * matrix.  m, v: dev f32[n] moment buffers owned by the caller (zero before the first step);

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libbns_gcn.so")
 
 EXPORTED = ["bns_workspace_bytes", "bns_create", "bns_destroy", "bns_last_error",
             "bns_sample_boundary", "bns_build_sampled_csr", "bns_gcn_layer_fwd",
-            "bns_gcn_layer_bwd", "bns_train_step", "bns_graph_capture", "bns_graph_replay", "bns_adam_update", "bns_cache_input_aggregate", "bns_ws_view",
+            "bns_gcn_layer_bwd", "bns_train_step", "bns_graph_capture", "bns_graph_replay", "bns_set_dropout", "bns_adam_update", "bns_cache_input_aggregate", "bns_ws_view",
             "bns_profile_enable", "bns_profile_read"]
 
 PHASES = ["sample", "build", "gather", "spmm_fwd", "gemm_fwd", "loss", "gemm_dw", "gemm_da",
@@ -86,6 +86,8 @@ def load_library():
     L.bns_graph_capture.argtypes = L.bns_train_step.argtypes
     L.bns_graph_replay.restype = i32
     L.bns_graph_replay.argtypes = [vp, i32, vp]
+    L.bns_set_dropout.restype = i32
+    L.bns_set_dropout.argtypes = [vp, C.c_double]
     L.bns_adam_update.restype = i32
     L.bns_adam_update.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_float, C.c_float, C.c_float, C.c_float, i32, vp]
     L.bns_cache_input_aggregate.restype = i32
@@ -206,6 +208,9 @@ class Context:
 
     def graph_replay(self, n_epochs):
         self._check(self._lib.bns_graph_replay(self._ctx, n_epochs, _stream()))
+
+    def set_dropout(self, q):
+        self._check(self._lib.bns_set_dropout(self._ctx, float(q)))
 
     def cache_input_aggregate(self, X):
         self._check(self._lib.bns_cache_input_aggregate(self._ctx, _ptr(X), _stream()))

@@ -76,6 +76,10 @@ struct bns_ctx {
   const int32_t *cur_row_ptr = nullptr, *cur_col_idx = nullptr, *cur_t_row_ptr = nullptr,
                 *cur_t_col_idx = nullptr;
   const float *cache_X = nullptr;  // features whose inner aggregate sits in ws.C0 (nullptr: none)
+  double drop_q = 0.0;             // dropout rate on hidden activations (0: none)
+  uint64_t cur_seed = 0;           // seed / epoch of the latest boundary sample: the dropout draw uses them
+  uint32_t cur_epoch = 0;
+  const uint32_t *cur_epoch_dev = nullptr;
   hipGraphExec_t graph_exec = nullptr;  // captured training step (bns_graph_capture)
   std::string err;
 };
@@ -197,6 +201,24 @@ struct PhaseTimer {
 bool bad_p(double p) { return !(p >= 0.0 && p <= 1.0); }
 float halo_scale(double p) { return p > 0.0 ? (float)(1.0 / p) : 0.f; }  // 1/p is never formed at p = 0
 
+// Dropout of hidden layer `layer` in the current epoch (off when the rate is 0 or the layer has no ReLU).
+Dropout dropout_of(const bns_ctx *ctx, int layer, bool relu) {
+  Dropout d;
+  if (!relu || ctx->drop_q <= 0.0) return d;
+  d.threshold = (uint64_t)std::floor((1.0 - ctx->drop_q) * 4294967296.0);
+  d.scale = (float)(1.0 / (1.0 - ctx->drop_q));
+  d.k0 = (uint32_t)ctx->cur_seed;
+  d.k1 = (uint32_t)(ctx->cur_seed >> 32) ^ 0x64726F70u;
+  d.c2 = ((uint32_t)ctx->part.part_id << 8) | (uint32_t)layer;
+  d.epoch = ctx->cur_epoch;
+  d.epoch_dev = ctx->cur_epoch_dev;
+  return d;
+}
+// Slope of a surviving hidden unit: 1/(1-q) under dropout, else 1.
+float mask_scale_of(const bns_ctx *ctx) {
+  return ctx->drop_q > 0.0 ? (float)(1.0 / (1.0 - ctx->drop_q)) : 1.f;
+}
+
 bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, const float *halo_h,
                           const float *W, float *A_saved, float *H_out, bool relu, hipStream_t s) {
   const int n_in = ctx->part.n_in, B = ctx->part.n_halo;
@@ -225,10 +247,11 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
   {
     PhaseTimer t(ctx, BNS_PHASE_GEMM_FWD, s);
     if (!sage) {
-      BNS_TRY("gemm_nn", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, relu, false, s));
+      BNS_TRY("gemm_nn", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, relu, false, dropout_of(ctx, layer, relu), s));
     } else {  // [z | h] [W_n ; W_s] = z W_n + h W_s
-      BNS_TRY("gemm_nn(nbr)", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, false, false, s));
-      BNS_TRY("gemm_nn(self)", gemm_nn(n_in, d_out, d_in, H_in, W + (size_t)d_in * d_out, H_out, relu, true, s));
+      BNS_TRY("gemm_nn(nbr)", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, false, false, Dropout{}, s));
+      BNS_TRY("gemm_nn(self)", gemm_nn(n_in, d_out, d_in, H_in, W + (size_t)d_in * d_out, H_out, relu, true,
+                                       dropout_of(ctx, layer, relu), s));
     }
   }
   return BNS_OK;
@@ -252,14 +275,14 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
     if (dH_in) {
       {
         PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
-        BNS_TRY("gemm_nt(nbr)", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, nullptr, nullptr, s));
-        BNS_TRY("gemm_nt(self)", gemm_nt(n_in, d_in, d_out, dZ, W + half, ctx->ws.G2, nullptr, nullptr, s));
+        BNS_TRY("gemm_nt(nbr)", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, nullptr, 1.f, nullptr, s));
+        BNS_TRY("gemm_nt(self)", gemm_nt(n_in, d_in, d_out, dZ, W + half, ctx->ws.G2, nullptr, 1.f, nullptr, s));
       }
       // dH_in = (gradient through the node's own feature) + mean^T (gradient of the neighbour mean)
       PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
       BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_in, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
                                    ctx->cur_kept, ctx->cur_n_kept, ctx->ws.inv_deg, nullptr, nullptr,
-                                   halo_scale(p), ctx->ws.G1, mask_src, ctx->ws.G2, true,
+                                   halo_scale(p), ctx->ws.G1, mask_src, mask_scale_of(ctx), ctx->ws.G2, true,
                                    ctx->ws.spmm_partials, dH_in, dhalo, s));
     }
     return BNS_OK;
@@ -275,22 +298,22 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
       PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
       BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_out, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
                                    ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_in,
-                                   ctx->ws.dis_halo, halo_scale(p), dZ, nullptr, nullptr, false,
+                                   ctx->ws.dis_halo, halo_scale(p), dZ, nullptr, 1.f, nullptr, false,
                                    ctx->ws.spmm_partials, G_in, G_halo, s));
     }
     PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
-    BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, G_in, W, dH_in, mask_src, nullptr, s));
+    BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, G_in, W, dH_in, mask_src, mask_scale_of(ctx), nullptr, s));
     if (G_halo && B > 0)
-      BNS_TRY("gemm_nt(halo)", gemm_nt(B, d_in, d_out, G_halo, W, dhalo, nullptr, ctx->cur_n_kept, s));
+      BNS_TRY("gemm_nt(halo)", gemm_nt(B, d_in, d_out, G_halo, W, dhalo, nullptr, 1.f, ctx->cur_n_kept, s));
   } else if (dH_in) {
     {
       PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
-      BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, nullptr, nullptr, s));
+      BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, nullptr, 1.f, nullptr, s));
     }
     PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
     BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_in, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
                                  ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_in,
-                                 ctx->ws.dis_halo, halo_scale(p), ctx->ws.G1, mask_src, nullptr, false,
+                                 ctx->ws.dis_halo, halo_scale(p), ctx->ws.G1, mask_src, mask_scale_of(ctx), nullptr, false,
                                  ctx->ws.spmm_partials, dH_in, dhalo, s));
   }
   return BNS_OK;
@@ -306,6 +329,9 @@ bns_status sample_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, const uint32
   ctx->cur_kept = kept_ids;
   ctx->cur_remap = remap;
   ctx->cur_n_kept = n_kept;
+  ctx->cur_seed = seed;
+  ctx->cur_epoch = epoch;
+  ctx->cur_epoch_dev = epoch_dev;
   return BNS_OK;
 }
 
@@ -423,7 +449,7 @@ bns_status bns_gcn_layer_bwd(bns_ctx *ctx, int32_t layer, double p, const float 
   const float *dZ = dH_out;
   if (H_out) {
     const int64_t n = (int64_t)ctx->part.n_in * ctx->dims[layer];
-    BNS_TRY("relu_mask", relu_mask(n, dH_out, H_out, ctx->ws.G0, s));
+    BNS_TRY("relu_mask", relu_mask(n, dH_out, H_out, mask_scale_of(ctx), ctx->ws.G0, s));
     dZ = ctx->ws.G0;
   }
   return layer_bwd_impl(ctx, layer, p, dZ, A_saved, H_in, W, dW, dH_in, dhalo, nullptr, s);
@@ -522,6 +548,13 @@ bns_status bns_graph_replay(bns_ctx *ctx, int32_t n_epochs, void *stream) {
   if (!ctx->graph_exec) return fail(ctx, BNS_EINVAL, "bns_graph_capture has not been called");
   for (int i = 0; i < n_epochs; ++i)
     BNS_TRY("hipGraphLaunch", hipGraphLaunch(ctx->graph_exec, static_cast<hipStream_t>(stream)));
+  return BNS_OK;
+}
+
+bns_status bns_set_dropout(bns_ctx *ctx, double q) {
+  if (!ctx) return BNS_EINVAL;
+  if (!(q >= 0.0 && q < 1.0)) return fail(ctx, BNS_EINVAL, "dropout rate must lie in [0, 1)");
+  ctx->drop_q = q;
   return BNS_OK;
 }
 

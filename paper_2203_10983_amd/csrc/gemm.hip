@@ -98,14 +98,17 @@ __device__ __forceinline__ void store_ncontig(const FragN<COLS> &f, float *__res
   }
 }
 
-// EPI: 0 = store, 1 = ReLU, 2 = zero where mask_src <= 0 (ReLU mask of the backward pass),
-// 3 = add to C, 4 = add to C then ReLU.
+// EPI: 0 = store, 1 = ReLU, 2 = zero where mask_src <= 0 and scale elsewhere (ReLU/dropout mask of
+// the backward pass), 3 = add to C, 4 = add to C then ReLU.  With EPI 1 or 4 and drop.scale != 0
+// the ReLU output goes through dropout: a lane owns four consecutive rows of one column per
+// accumulator quad, which is exactly one Philox call.
 // m_dev (nullable): the row count lives on the device (*m_dev <= M); tiles past it do nothing.
 template <int BN, bool A_KCONTIG, bool B_KCONTIG, int EPI>
 __global__ void __launch_bounds__(kGemmThreads, 4)
 gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const float *__restrict__ B,
             int ldb, float *__restrict__ C, int ldc, int k_chunk, bool vec_a, bool vec_b,
-            const float *__restrict__ mask_src, const int *__restrict__ m_dev) {
+            const float *__restrict__ mask_src, float mask_scale, const int *__restrict__ m_dev,
+            const Dropout drop) {
   constexpr int LDA = BM + 4, LDB = BN + 4;  // row strides of the staged tiles (16-byte aligned rows)
   constexpr int TI = BN == 128 ? 2 : 1;      // 32-row MFMA tiles per wavefront
   const int m_full = M;
@@ -184,14 +187,27 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
       const int col = bn0 + wn + j * 32 + l32;
       if (col >= N) continue;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = bm0 + wm + i * 32 + (r >> 2) * 8 + lhi * 4 + (r & 3);
-        if (row < M) {
-          float x = acc[i][j][r];
-          if (EPI == 3 || EPI == 4) x += C[(size_t)row * ldc + col];
-          if (EPI == 1 || EPI == 4) x = fmaxf(x, 0.f);
-          if (EPI == 2) x = mask_src[(size_t)row * ldc + col] > 0.f ? x : 0.f;
-          C[(size_t)row * ldc + col] = x;
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int row4 = bm0 + wm + i * 32 + q4 * 8 + lhi * 4;  // a multiple of 4
+        uint32_t u[4] = {0u, 0u, 0u, 0u};
+        if ((EPI == 1 || EPI == 4) && drop.scale != 0.f && row4 < M) {
+          u[0] = (uint32_t)(row4 >> 2); u[1] = (uint32_t)col; u[2] = drop.c2;
+          u[3] = drop.epoch_dev ? *drop.epoch_dev : drop.epoch;
+          philox4x32_10(u[0], u[1], u[2], u[3], drop.k0, drop.k1);
+        }
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const int row = row4 + rr;
+          if (row < M) {
+            float x = acc[i][j][q4 * 4 + rr];
+            if (EPI == 3 || EPI == 4) x += C[(size_t)row * ldc + col];
+            if (EPI == 1 || EPI == 4) {
+              x = fmaxf(x, 0.f);
+              if (drop.scale != 0.f) x = (uint64_t)u[rr] < drop.threshold ? x * drop.scale : 0.f;
+            }
+            if (EPI == 2) x = mask_src[(size_t)row * ldc + col] > 0.f ? x * mask_scale : 0.f;
+            C[(size_t)row * ldc + col] = x;
+          }
         }
       }
     }
@@ -215,28 +231,28 @@ static inline unsigned n_tiles(int M, int N, int bn) {
   } while (0)
 
 hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   bool relu, bool accumulate, hipStream_t s) {
+                   bool relu, bool accumulate, const Dropout &drop, hipStream_t s) {
   const int bn = pick_bn(N);
   const unsigned tiles = n_tiles(M, N, bn);
   if (tiles == 0) return hipSuccess;
   const bool va = (K % 4 == 0) && aligned16(A), vb = (N % 4 == 0) && aligned16(B);
   const dim3 grid(tiles, 1);
-  if (accumulate && relu) BNS_GEMM_LAUNCH(true, false, 4, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, nullptr);
-  else if (accumulate) BNS_GEMM_LAUNCH(true, false, 3, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, nullptr);
-  else if (relu) BNS_GEMM_LAUNCH(true, false, 1, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, nullptr);
-  else BNS_GEMM_LAUNCH(true, false, 0, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, nullptr);
+  if (accumulate && relu) BNS_GEMM_LAUNCH(true, false, 4, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, nullptr, drop);
+  else if (accumulate) BNS_GEMM_LAUNCH(true, false, 3, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, nullptr, drop);
+  else if (relu) BNS_GEMM_LAUNCH(true, false, 1, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, nullptr, drop);
+  else BNS_GEMM_LAUNCH(true, false, 0, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, nullptr, drop);
   return hipGetLastError();
 }
 
 hipError_t gemm_nt(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   const float *mask_src, const int32_t *m_dev, hipStream_t s) {
+                   const float *mask_src, float mask_scale, const int32_t *m_dev, hipStream_t s) {
   const int bn = pick_bn(N);
   const unsigned tiles = n_tiles(M, N, bn);
   if (tiles == 0) return hipSuccess;
   const bool va = (K % 4 == 0) && aligned16(A), vb = (K % 4 == 0) && aligned16(B);
   const dim3 grid(tiles, 1);
-  if (mask_src) BNS_GEMM_LAUNCH(true, true, 2, grid, M, N, K, A, K, B, K, C, N, K, va, vb, mask_src, m_dev);
-  else BNS_GEMM_LAUNCH(true, true, 0, grid, M, N, K, A, K, B, K, C, N, K, va, vb, nullptr, m_dev);
+  if (mask_src) BNS_GEMM_LAUNCH(true, true, 2, grid, M, N, K, A, K, B, K, C, N, K, va, vb, mask_src, mask_scale, m_dev, Dropout{});
+  else BNS_GEMM_LAUNCH(true, true, 0, grid, M, N, K, A, K, B, K, C, N, K, va, vb, nullptr, 1.f, m_dev, Dropout{});
   return hipGetLastError();
 }
 
@@ -288,7 +304,7 @@ hipError_t gemm_tn_splitk(int32_t M, int32_t N, int32_t K, const float *A, const
   const int64_t mn = (int64_t)M * N;
   float *dst = splits == 1 ? C : partials;
   const dim3 grid(tiles, splits);
-  BNS_GEMM_LAUNCH(false, false, 0, grid, M, N, K, A, M, B, N, dst, N, chunk, va, vb, nullptr, nullptr);
+  BNS_GEMM_LAUNCH(false, false, 0, grid, M, N, K, A, M, B, N, dst, N, chunk, va, vb, nullptr, 1.f, nullptr, Dropout{});
   // grouped, fixed-order reduction: partials -> level 2 -> ... -> C
   float *cur = partials;
   float *nxt = partials + (size_t)splits * mn;

@@ -96,26 +96,38 @@ hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t 
                     const float *H_in, const float *Hu, float *partials, float *A,
                     const SpmmRowPart &part, hipStream_t s);
 // For stacked column u < n_in + *n_kept:  g = sum_{v in t_row u} w_col[v] dA[v,:];
-//   u <  n_in: dH_in[u,:] = row_scale[u] * (init[u,:] + g)  (zeroed where mask_src[u,:] <= 0 if given)
+//   u <  n_in: dH_in[u,:] = row_scale[u] * (init[u,:] + g)  (if mask_src is given: zeroed where
+//              mask_src[u,:] <= 0, multiplied by mask_scale elsewhere)
 //   u >= n_in: dhalo[u-n_in,:] = s_halo * dis_halo[kept_ids[u-n_in]] * g   (skipped if dhalo null)
 // row_scale, dis_halo, init nullable.  plan: segmentation of the transposed inner-inner block.
 hipError_t spmm_bwd(const SegPlan &plan, int32_t n_in, int32_t n_halo, int32_t d,
                     const int32_t *t_row_ptr, const int32_t *t_col_idx, const int32_t *kept_ids,
                     const int32_t *n_kept, const float *w_col, const float *row_scale,
                     const float *dis_halo, float s_halo, const float *dA, const float *mask_src,
-                    const float *init, bool skip_self, float *partials, float *dH_in, float *dhalo,
-                    hipStream_t s);
+                    float mask_scale, const float *init, bool skip_self, float *partials, float *dH_in,
+                    float *dhalo, hipStream_t s);
 
 // ---- gemm.hip (Eq. 2 and its backward; fp32 MFMA) ----------------------------------------------
-// C[M,N] = A[M,K] B[K,N] (+ the previous C if accumulate), then optional ReLU.
+// Dropout on a hidden layer's output (training set-up of Section 4): element (row, col) is kept iff
+// word (row mod 4) of Philox-4x32-10 on the counter (row div 4, col, c2, epoch) under key (k0, k1)
+// is below `threshold`; kept elements are multiplied by `scale` = 1/(1-q).  scale == 0: no dropout.
+struct Dropout {
+  uint64_t threshold = 0;
+  float scale = 0.f;
+  uint32_t k0 = 0, k1 = 0, c2 = 0, epoch = 0;
+  const uint32_t *epoch_dev = nullptr;  // nullable: the epoch index is read from device memory
+};
+// C[M,N] = A[M,K] B[K,N] (+ the previous C if accumulate), then optional ReLU (followed by dropout
+// when drop.scale != 0).
 hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   bool relu, bool accumulate, hipStream_t s);
+                   bool relu, bool accumulate, const Dropout &drop, hipStream_t s);
 // inv[i] = deg[i] > 1 ? 1 / (deg[i] - 1) : 0   (deg counts the self-loop)
 hipError_t degree_inverse(const int32_t *deg, int32_t n, float *inv, hipStream_t s);
-// C[M,N] = A[M,K] B[N,K]^T.  mask_src (nullable, [M,N]): C is zeroed where mask_src <= 0.
+// C[M,N] = A[M,K] B[N,K]^T.  mask_src (nullable, [M,N]): C is zeroed where mask_src <= 0 and
+// multiplied by mask_scale elsewhere.
 // m_dev (nullable): device-side row count, *m_dev <= M; rows past it are not touched.
 hipError_t gemm_nt(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   const float *mask_src, const int32_t *m_dev, hipStream_t s);
+                   const float *mask_src, float mask_scale, const int32_t *m_dev, hipStream_t s);
 // C[M,N] = A[K,M]^T B[K,N] with K split over the grid; partials: scratch f32[splits*M*N],
 // summed in a fixed order.  splitk_splits() gives the split count used for (M,N,K).
 int32_t splitk_splits(int32_t M, int32_t N, int32_t K);
@@ -128,8 +140,8 @@ hipError_t loss_softmax_ce(int32_t n, int32_t C, const float *logits, const int3
                            float *dZ, float *partials, float *loss, hipStream_t s);
 hipError_t loss_sigmoid_bce(int32_t n, int32_t C, const float *logits, const uint8_t *labels,
                             float *dZ, float *partials, float *loss, hipStream_t s);
-// out = dH where H > 0 else 0
-hipError_t relu_mask(int64_t n, const float *dH, const float *H, float *out, hipStream_t s);
+// out = scale * dH where H > 0 else 0
+hipError_t relu_mask(int64_t n, const float *dH, const float *H, float scale, float *out, hipStream_t s);
 // Adam step t (1-based) on n weights; m, v are the caller's moment buffers.
 hipError_t adam_update(int64_t n, float *W, const float *dW, float *m, float *v, float lr, float b1,
                        float b2, float eps, int32_t t, hipStream_t s);

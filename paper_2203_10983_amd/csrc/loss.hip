@@ -133,18 +133,18 @@ hipError_t loss_sigmoid_bce(int32_t n, int32_t C, const float *logits, const uin
 }
 
 __global__ void __launch_bounds__(kT)
-relu_mask_kernel(int64_t n, const float *__restrict__ dH, const float *__restrict__ H,
+relu_mask_kernel(int64_t n, const float *__restrict__ dH, const float *__restrict__ H, float scale,
                  float *__restrict__ out) {
   const int64_t stride = (int64_t)gridDim.x * kT;
   for (int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x; i < n; i += stride)
-    out[i] = H[i] > 0.f ? dH[i] : 0.f;
+    out[i] = H[i] > 0.f ? dH[i] * scale : 0.f;
 }
 
-hipError_t relu_mask(int64_t n, const float *dH, const float *H, float *out, hipStream_t s) {
+hipError_t relu_mask(int64_t n, const float *dH, const float *H, float scale, float *out, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   int64_t blocks = (n + kT * 4 - 1) / (kT * 4);
   if (blocks > 65536) blocks = 65536;
-  relu_mask_kernel<<<(unsigned)blocks, kT, 0, s>>>(n, dH, H, out);
+  relu_mask_kernel<<<(unsigned)blocks, kT, 0, s>>>(n, dH, H, scale, out);
   return hipGetLastError();
 }
 

@@ -45,6 +45,7 @@ struct SpmmArgs {
   float *out0, *out1;
   const float *out_scale0;
   const float *mask_src;
+  float mask_scale;            // factor on the elements that pass the mask
   const int32_t *kept_ids;     // out1 row r is scaled by s_halo * dis_halo[kept_ids[r]]
   const float *dis_halo;
   float s_halo;
@@ -101,7 +102,7 @@ __device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, i
         const V m = reinterpret_cast<const V *>(mask)[iv];
         const float *pm = reinterpret_cast<const float *>(&m);
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) po[i] = pm[i] > 0.f ? po[i] : 0.f;
+        for (int i = 0; i < VEC; ++i) po[i] = pm[i] > 0.f ? po[i] * a.mask_scale : 0.f;
       }
       reinterpret_cast<V *>(out)[iv] = o;
     }
@@ -343,7 +344,7 @@ hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t 
   a.plan = plan; a.n_extra_dev = nullptr; a.d = d;
   a.row_ptr = row_ptr; a.col_idx = col_idx; a.n_split = n_in;
   a.src0 = H_in; a.src1 = Hu; a.w_col = w_col; a.partials = partials;
-  a.out0 = A; a.out1 = nullptr; a.out_scale0 = row_scale; a.mask_src = nullptr;
+  a.out0 = A; a.out1 = nullptr; a.out_scale0 = row_scale; a.mask_src = nullptr; a.mask_scale = 1.f;
   a.kept_ids = nullptr; a.dis_halo = nullptr; a.s_halo = 0.f;
   a.row_skip = part.row_skip; a.row_take = part.row_take; a.init = part.init;
   a.skip_self = part.skip_self;
@@ -354,14 +355,15 @@ hipError_t spmm_bwd(const SegPlan &plan, int32_t n_in, int32_t n_halo, int32_t d
                     const int32_t *t_row_ptr, const int32_t *t_col_idx, const int32_t *kept_ids,
                     const int32_t *n_kept, const float *w_col, const float *row_scale,
                     const float *dis_halo, float s_halo, const float *dA, const float *mask_src,
-                    const float *init, bool skip_self, float *partials, float *dH_in, float *dhalo,
-                    hipStream_t s) {
+                    float mask_scale, const float *init, bool skip_self, float *partials, float *dH_in,
+                    float *dhalo, hipStream_t s) {
   SpmmArgs a{};
   const bool halo_rows = dhalo && n_halo > 0;
   a.plan = plan; a.n_extra_dev = halo_rows ? n_kept : nullptr; a.d = d;
   a.row_ptr = t_row_ptr; a.col_idx = t_col_idx; a.n_split = n_in;
   a.src0 = dA; a.src1 = nullptr; a.w_col = w_col; a.partials = partials;
   a.out0 = dH_in; a.out1 = dhalo; a.out_scale0 = row_scale; a.mask_src = mask_src;
+  a.mask_scale = mask_scale;
   a.kept_ids = kept_ids; a.dis_halo = dis_halo; a.s_halo = s_halo;
   a.init = init; a.skip_self = skip_self;
   return launch_spmm(a, (int64_t)plan.n_seg + (halo_rows ? n_halo : 0), s);

@@ -246,6 +246,16 @@ def test_train_step_end_to_end(case):
         for l in range(L):
             g_gpu, g_ref = dW[l].cpu().numpy().astype(np.float64), ref["dW"][l]
             assert np.abs(g_gpu - g_ref).max() <= 2e-2 * np.abs(g_ref).max(), f"dW[{l}] (with ties)"
+        # (d) the oracle's backward pass on the activation pattern the device produced: no ambiguity left
+        H_dev = [w.X.astype(np.float64)] + [view(pkg.VIEW_H, l, torch.float32).cpu().numpy()
+                                            .reshape(P.n_in, w.dims[l]).astype(np.float64) for l in range(1, L + 1)]
+        dZ_dev = orc.loss_and_grad(H_dev[L], w.labels, w.loss_kind)[1]
+        bwd = orc.backward if c.kind == 0 else orc.backward_sage
+        dW2, dhalo2, _ = bwd(P, ref["sub"], ref["A"], H_dev, w.W, dZ_dev, p)
+        errs2 = [rel_err(dW[l].cpu().numpy(), dW2[l]) for l in range(L)]
+        errs2 += [rel_err(dhalo[l][:n_u].cpu().numpy(), dhalo2[l]) for l in range(1, L)]
+        _log(f"[test]   grads against the oracle's backward on the device's activation pattern: {max(errs2):.2e}")
+        assert max(errs2) <= 1e-4, errs2
     for l in range(1, L):
         assert np.all(dhalo[l][n_u:].cpu().numpy() == 0.0)
 
@@ -435,4 +445,111 @@ def test_graph_replay_equals_eager_epochs(cfg, scale, kind, cached):
         assert torch.equal(W[l], W2[l])
     if cached:
         ctx.cache_input_aggregate(None)
+    ctx.close()
+
+
+@pytest.mark.parametrize("cfg,scale,kind,q", [(1, 1, 0, 0.5), (1, 1, 1, 0.3), (3, 32, 0, 0.5), (4, 16, 0, 0.1),
+                                              (5, 64, 1, 0.5), (5, 1, 0, 0.5)],
+                         ids=["tiny-gcn-q0.5", "tiny-sage-q0.3", "cfg3s32-gcn-q0.5", "cfg4s16-gcn-q0.1",
+                              "cfg5s64-sage-q0.5", "cfg5-gcn-q0.5"])
+def test_dropout_against_oracle(cfg, scale, kind, q):
+    """Dropout on the hidden activations (training set-up of Section 4): same element draws as the
+    oracle (bit-exact zero pattern away from ReLU ties), activations, loss and gradients within
+    tolerance; the layer calls use the seed and epoch of the latest sample; graph replays draw a
+    fresh mask per epoch."""
+    import torch
+    import paper_2203_10983_amd as pkg
+    from bns_inputs.workloads import sage_weights
+    w = make_workload(cfg, scale=scale)
+    if kind == 1:
+        w.W = sage_weights(77, w.dims)
+    P, L = w.part, w.n_layers
+    p, epoch = 0.25, 5
+    _log(f"[test] dropout cfg={cfg} scale={scale} kind={kind} q={q}")
+    dev = torch.device("cuda:0")
+    f32 = dict(dtype=torch.float32, device=dev)
+    ctx = pkg.Context(P, w.dims, w.loss_kind, device=dev, layer_kind=kind)
+    with pytest.raises(RuntimeError):
+        ctx.set_dropout(1.0)
+    ctx.set_dropout(q)
+    X = torch.from_numpy(w.X).to(dev)
+    halo_h = [torch.from_numpy(h).to(dev) for h in w.halo_h]
+    labels = torch.from_numpy(w.labels).to(dev)
+    W = [torch.from_numpy(x).to(dev) for x in w.W]
+    dW = [torch.empty_like(x) for x in W]
+    dhalo = [None] + [torch.zeros(P.n_halo + 1, w.dims[l], **f32) for l in range(1, L)]
+    loss = torch.zeros(1, **f32)
+    ctx.train_step(SAMPLING_SEED, epoch, p, X, halo_h, labels, W, dW, dhalo, loss, 0.0)
+    torch.cuda.synchronize()
+    ref = orc.step(P, w.loss_kind, w.X, w.halo_h, w.labels, w.W, SAMPLING_SEED, epoch, p, layer_kind=kind,
+                   dropout=q)
+    n_u = ref["sub"]["kept_ids"].size
+    ties = 0
+    for l in range(1, L + 1):
+        H = ctx.ws_tensor(pkg.VIEW_H, l, torch.float32).cpu().numpy().reshape(P.n_in, w.dims[l])
+        assert_close(H, ref["H"][l], f"H[{l}]")
+        if l < L:
+            near = np.abs(ref["Z"][l]) <= 1e-5 * np.abs(ref["Z"][l]).max()
+            ties += tie_count(ref["Z"][l])
+            assert np.array_equal((H > 0)[~near], (ref["H"][l] > 0)[~near]), f"zero pattern of H[{l}]"
+            kept_frac = (ref["H"][l] > 0).sum() / max((ref["Z"][l] > 0).sum(), 1)
+            assert abs(kept_frac - (1 - q)) < 0.05
+    assert abs(float(loss[0]) - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+    errs = [rel_err(dW[l].cpu().numpy(), ref["dW"][l]) for l in range(L)]
+    errs += [rel_err(dhalo[l][:n_u].cpu().numpy(), ref["dhalo"][l]) for l in range(1, L)]
+    _log(f"[test]   grads worst {max(errs):.2e}; ties {ties}")
+    if ties == 0:
+        assert max(errs) <= 1e-4, errs
+    else:
+        # some ReLUs are decided by rounding: take the oracle's backward pass on the activation
+        # pattern the device actually produced (its own H), which removes the ambiguity
+        H_dev = [None] + [ctx.ws_tensor(pkg.VIEW_H, l, torch.float32).cpu().numpy()
+                          .reshape(P.n_in, w.dims[l]).astype(np.float64) for l in range(1, L + 1)]
+        H_dev[0] = w.X.astype(np.float64)
+        dZ_dev = orc.loss_and_grad(H_dev[L], w.labels, w.loss_kind)[1]
+        bwd = orc.backward if kind == 0 else orc.backward_sage
+        dW2, dhalo2, _ = bwd(P, ref["sub"], ref["A"], H_dev, w.W, dZ_dev, p, drop_scale=orc.dropout_scale(q))
+        errs2 = [rel_err(dW[l].cpu().numpy(), dW2[l]) for l in range(L)]
+        errs2 += [rel_err(dhalo[l][:n_u].cpu().numpy(), dhalo2[l]) for l in range(1, L)]
+        _log(f"[test]   grads against the oracle's backward on the device's activation pattern: {max(errs2):.2e}")
+        assert max(errs2) <= 1e-4, errs2
+
+    # the layer calls: forward of layer 1 and its backward from the oracle's upstream gradient
+    i32 = dict(dtype=torch.int32, device=dev)
+    bufs = dict(kept=torch.empty(P.n_halo + 1, **i32), remap=torch.empty(P.n_halo + 1, **i32),
+                n_kept=torch.zeros(1, **i32), row_ptr=torch.empty(P.n_in + 1, **i32),
+                col_idx=torch.empty(P.nnz0, **i32), t_row_ptr=torch.empty(P.n_in + P.n_halo + 1, **i32),
+                t_col_idx=torch.empty(P.nnz0, **i32), nnz=torch.zeros(1, **i32))
+    ctx.sample_boundary(SAMPLING_SEED, epoch, p, bufs["kept"], bufs["remap"], bufs["n_kept"])
+    ctx.build_sampled_csr(bufs["row_ptr"], bufs["col_idx"], bufs["t_row_ptr"], bufs["t_col_idx"], bufs["nnz"])
+    A1 = torch.empty(P.n_in, w.dims[0], **f32)
+    H1 = torch.empty(P.n_in, w.dims[1], **f32)
+    ctx.gcn_layer_fwd(1, p, X, halo_h[0], W[0], A1, H1, 1)
+    torch.cuda.synchronize()
+    assert_close(H1.cpu().numpy(), ref["H"][1], "layer call H[1]")
+    dW1 = torch.empty_like(W[0])
+    to32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)  # noqa: E731
+    ctx.gcn_layer_bwd(1, p, to32(ref["dH"][1]), to32(ref["H"][1]), to32(ref["A"][1]), X, W[0], dW1, None, None)
+    torch.cuda.synchronize()
+    assert_close(dW1.cpu().numpy(), ref["dW"][0], "layer call dW[1]")
+
+    if scale > 1 or cfg == 1:   # graph replay: a fresh mask per epoch, bit-identical to eager steps
+        want = []
+        for e in (epoch, epoch + 1):
+            ctx.train_step(SAMPLING_SEED, e, p, X, halo_h, labels, W, dW, dhalo, loss, 0.0)
+            torch.cuda.synchronize()
+            want.append((loss.clone(), [x.clone() for x in dW]))
+        assert not torch.equal(want[0][1][0], want[1][1][0])
+        side = torch.cuda.Stream(device=dev)
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            ctx.graph_capture(SAMPLING_SEED, epoch, p, X, halo_h, labels, W, dW, dhalo, loss, 0.0)
+        for e in range(2):
+            with torch.cuda.stream(side):
+                ctx.graph_replay(1)
+            side.synchronize()
+            assert torch.equal(loss, want[e][0])
+            for a, b in zip(dW, want[e][1]):
+                assert torch.equal(a, b)
+    bufs.clear()
     ctx.close()
