@@ -142,6 +142,7 @@ size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, La
     pl.seg_row = c.take<int32_t>(seg_max_segments(n_in, nnz));
     pl.part_ptr = c.take<int32_t>(n_in + 1);
     pl.mrow = c.take<int32_t>(seg_max_multi(nnz));
+    pl.part_row = c.take<int32_t>(seg_max_parts(nnz));
     pl.n_seg = pl.n_part = pl.n_multi = 0;
   }
   w.seg_tmp_a = c.take<int32_t>(n_in + 1);
@@ -230,19 +231,31 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
     BNS_TRY("halo_gather", halo_gather(halo_h, ctx->cur_kept, ctx->cur_n_kept, B,
                                        sage ? nullptr : ctx->ws.dis_halo, halo_scale(p), d_in, ctx->ws.Hu, s));
   }
+  SpmmRowPart part;
+  part.skip_self = sage;
+  if (layer == 1 && ctx->cache_X != nullptr && ctx->cache_X == H_in) {
+    // inner neighbours are the same every epoch: their sum is cached, only the kept boundary
+    // tail of each row is aggregated now
+    part.row_skip = ctx->ws.split.n_inner;
+    part.init = ctx->ws.C0;
+  }
+  const float *w_col = sage ? nullptr : ctx->ws.dis_in;
+  const float *row_scale = sage ? ctx->ws.inv_deg : ctx->ws.dis_in;
+  if (!sage && spmm_gemm_fwd_supported(d_in)) {
+    // aggregate and update in one kernel; the rows cut into several segments are finished first
+    PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
+    BNS_TRY("spmm_fwd(long rows)", spmm_fwd(ctx->ws.plan_f, n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx, w_col,
+                                            row_scale, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part,
+                                            true, s));
+    BNS_TRY("spmm_gemm_fwd", spmm_gemm_fwd(ctx->ws.plan_f, n_in, d_in, d_out, ctx->cur_row_ptr, ctx->cur_col_idx,
+                                           w_col, row_scale, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved,
+                                           part, W, H_out, relu, dropout_of(ctx, layer, relu), s));
+    return BNS_OK;
+  }
   {
     PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
-    SpmmRowPart part;
-    part.skip_self = sage;
-    if (layer == 1 && ctx->cache_X != nullptr && ctx->cache_X == H_in) {
-      // inner neighbours are the same every epoch: their sum is cached, only the kept boundary
-      // tail of each row is aggregated now
-      part.row_skip = ctx->ws.split.n_inner;
-      part.init = ctx->ws.C0;
-    }
-    BNS_TRY("spmm_fwd", spmm_fwd(ctx->ws.plan_f, n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx,
-                                 sage ? nullptr : ctx->ws.dis_in, sage ? ctx->ws.inv_deg : ctx->ws.dis_in,
-                                 H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part, s));
+    BNS_TRY("spmm_fwd", spmm_fwd(ctx->ws.plan_f, n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx, w_col, row_scale,
+                                 H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part, false, s));
   }
   {
     PhaseTimer t(ctx, BNS_PHASE_GEMM_FWD, s);
@@ -265,6 +278,10 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
                           const float *mask_src, hipStream_t s) {
   const int n_in = ctx->part.n_in, B = ctx->part.n_halo;
   const int d_in = ctx->dims[layer - 1], d_out = ctx->dims[layer];
+  // slope of the surviving hidden units of the layer below (dropout); it multiplies the masked
+  // gradient only.  Where the transposed aggregate applies the mask, the factor rides on its
+  // input (the product with W^T) and is divided out of the boundary rows, which are not masked.
+  const float ms = mask_src ? mask_scale_of(ctx) : 1.f;
   if (ctx->layer_kind == 1) {
     const size_t half = (size_t)d_in * d_out;
     {
@@ -275,14 +292,14 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
     if (dH_in) {
       {
         PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
-        BNS_TRY("gemm_nt(nbr)", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, nullptr, 1.f, nullptr, s));
-        BNS_TRY("gemm_nt(self)", gemm_nt(n_in, d_in, d_out, dZ, W + half, ctx->ws.G2, nullptr, 1.f, nullptr, s));
+        BNS_TRY("gemm_nt(nbr)", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, nullptr, ms, nullptr, s));
+        BNS_TRY("gemm_nt(self)", gemm_nt(n_in, d_in, d_out, dZ, W + half, ctx->ws.G2, nullptr, ms, nullptr, s));
       }
       // dH_in = (gradient through the node's own feature) + mean^T (gradient of the neighbour mean)
       PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
       BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_in, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
                                    ctx->cur_kept, ctx->cur_n_kept, ctx->ws.inv_deg, nullptr, nullptr,
-                                   halo_scale(p), ctx->ws.G1, mask_src, mask_scale_of(ctx), ctx->ws.G2, true,
+                                   halo_scale(p) / ms, ctx->ws.G1, mask_src, ctx->ws.G2, true,
                                    ctx->ws.spmm_partials, dH_in, dhalo, s));
     }
     return BNS_OK;
@@ -298,22 +315,22 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
       PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
       BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_out, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
                                    ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_in,
-                                   ctx->ws.dis_halo, halo_scale(p), dZ, nullptr, 1.f, nullptr, false,
+                                   ctx->ws.dis_halo, halo_scale(p), dZ, nullptr, nullptr, false,
                                    ctx->ws.spmm_partials, G_in, G_halo, s));
     }
     PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
-    BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, G_in, W, dH_in, mask_src, mask_scale_of(ctx), nullptr, s));
+    BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, G_in, W, dH_in, mask_src, ms, nullptr, s));
     if (G_halo && B > 0)
       BNS_TRY("gemm_nt(halo)", gemm_nt(B, d_in, d_out, G_halo, W, dhalo, nullptr, 1.f, ctx->cur_n_kept, s));
   } else if (dH_in) {
     {
       PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
-      BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, nullptr, 1.f, nullptr, s));
+      BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, nullptr, ms, nullptr, s));
     }
     PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
     BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_in, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
                                  ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_in,
-                                 ctx->ws.dis_halo, halo_scale(p), ctx->ws.G1, mask_src, mask_scale_of(ctx), nullptr, false,
+                                 ctx->ws.dis_halo, halo_scale(p) / ms, ctx->ws.G1, mask_src, nullptr, false,
                                  ctx->ws.spmm_partials, dH_in, dhalo, s));
   }
   return BNS_OK;
@@ -580,7 +597,7 @@ bns_status bns_cache_input_aggregate(bns_ctx *ctx, const float *X, void *stream)
   part.skip_self = sage;
   BNS_TRY("spmm_fwd(cache)", spmm_fwd(ctx->ws.plan_f, ctx->part.n_in, ctx->dims[0], ctx->part.row_ptr0,
                                       ctx->part.col0, sage ? nullptr : ctx->ws.dis_in, nullptr, X, nullptr,
-                                      ctx->ws.spmm_partials, ctx->ws.C0, part, s));
+                                      ctx->ws.spmm_partials, ctx->ws.C0, part, false, s));
   ctx->cache_X = X;
   return BNS_OK;
 }

@@ -98,8 +98,8 @@ __device__ __forceinline__ void store_ncontig(const FragN<COLS> &f, float *__res
   }
 }
 
-// EPI: 0 = store, 1 = ReLU, 2 = zero where mask_src <= 0 and scale elsewhere (ReLU/dropout mask of
-// the backward pass), 3 = add to C, 4 = add to C then ReLU.  With EPI 1 or 4 and drop.scale != 0
+// EPI: 0 = store alpha * product, 1 = ReLU, 2 = zero where mask_src <= 0, alpha * product elsewhere
+// (ReLU/dropout mask of the backward pass), 3 = add to C, 4 = add to C then ReLU.  With EPI 1 or 4 and drop.scale != 0
 // the ReLU output goes through dropout: a lane owns four consecutive rows of one column per
 // accumulator quad, which is exactly one Philox call.
 // m_dev (nullable): the row count lives on the device (*m_dev <= M); tiles past it do nothing.
@@ -107,7 +107,7 @@ template <int BN, bool A_KCONTIG, bool B_KCONTIG, int EPI>
 __global__ void __launch_bounds__(kGemmThreads, 4)
 gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const float *__restrict__ B,
             int ldb, float *__restrict__ C, int ldc, int k_chunk, bool vec_a, bool vec_b,
-            const float *__restrict__ mask_src, float mask_scale, const int *__restrict__ m_dev,
+            const float *__restrict__ mask_src, float alpha, const int *__restrict__ m_dev,
             const Dropout drop) {
   constexpr int LDA = BM + 4, LDB = BN + 4;  // row strides of the staged tiles (16-byte aligned rows)
   constexpr int TI = BN == 128 ? 2 : 1;      // 32-row MFMA tiles per wavefront
@@ -205,7 +205,8 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
               x = fmaxf(x, 0.f);
               if (drop.scale != 0.f) x = (uint64_t)u[rr] < drop.threshold ? x * drop.scale : 0.f;
             }
-            if (EPI == 2) x = mask_src[(size_t)row * ldc + col] > 0.f ? x * mask_scale : 0.f;
+            if (EPI == 2) x = mask_src[(size_t)row * ldc + col] > 0.f ? x * alpha : 0.f;
+            if (EPI == 0) x *= alpha;
             C[(size_t)row * ldc + col] = x;
           }
         }
@@ -245,14 +246,14 @@ hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float 
 }
 
 hipError_t gemm_nt(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   const float *mask_src, float mask_scale, const int32_t *m_dev, hipStream_t s) {
+                   const float *mask_src, float alpha, const int32_t *m_dev, hipStream_t s) {
   const int bn = pick_bn(N);
   const unsigned tiles = n_tiles(M, N, bn);
   if (tiles == 0) return hipSuccess;
   const bool va = (K % 4 == 0) && aligned16(A), vb = (K % 4 == 0) && aligned16(B);
   const dim3 grid(tiles, 1);
-  if (mask_src) BNS_GEMM_LAUNCH(true, true, 2, grid, M, N, K, A, K, B, K, C, N, K, va, vb, mask_src, mask_scale, m_dev, Dropout{});
-  else BNS_GEMM_LAUNCH(true, true, 0, grid, M, N, K, A, K, B, K, C, N, K, va, vb, nullptr, 1.f, m_dev, Dropout{});
+  if (mask_src) BNS_GEMM_LAUNCH(true, true, 2, grid, M, N, K, A, K, B, K, C, N, K, va, vb, mask_src, alpha, m_dev, Dropout{});
+  else BNS_GEMM_LAUNCH(true, true, 0, grid, M, N, K, A, K, B, K, C, N, K, va, vb, nullptr, alpha, m_dev, Dropout{});
   return hipGetLastError();
 }
 

@@ -55,6 +55,8 @@ hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
                                 int32_t *tile_sums, int32_t *t_row_ptr, int32_t *t_col_idx,
                                 hipStream_t s);
 
+struct Dropout;  // defined with the GEMMs below
+
 // ---- spmm.hip (Eq. 1 in the sampled form of Appendix A, and its transpose) ---------------------
 constexpr int kSegLen = 256;  // a wavefront aggregates at most this many neighbours
 // Static cut of the rows of a CSR pattern into segments of <= kSegLen entries (by the static row
@@ -65,6 +67,7 @@ struct SegPlan {
   int32_t *seg_row;   // int32[n_seg]    row of each segment
   int32_t *part_ptr;  // int32[n_rows+1] first partial-sum slot of each multi-segment row
   int32_t *mrow;      // int32[n_multi]  rows with more than one segment
+  int32_t *part_row;  // int32[n_part]   row of each partial-sum slot
   int32_t n_seg, n_part, n_multi;  // host copies of the totals
   int32_t avg_len;                 // entries per row of the static pattern (launch heuristics)
 };
@@ -94,18 +97,28 @@ struct SpmmRowPart {
 hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
                     const int32_t *col_idx, const float *w_col, const float *row_scale,
                     const float *H_in, const float *Hu, float *partials, float *A,
-                    const SpmmRowPart &part, hipStream_t s);
+                    const SpmmRowPart &part, bool long_rows_only, hipStream_t s);
+// Aggregate and update of one GCN layer in one kernel (Eq. 1 then Eq. 2): a workgroup aggregates 64
+// rows into LDS (and stores them to A, which the backward pass needs), then multiplies the tile by
+// W on the matrix cores while other workgroups of the same compute unit keep gathering.  Rows cut
+// into several segments must have been finished before by spmm_fwd(..., long_rows_only = true).
+// Needs d_in % 4 == 0 and 64 < d_in <= 128 (spmm_gemm_fwd_supported).
+bool spmm_gemm_fwd_supported(int32_t d_in);
+hipError_t spmm_gemm_fwd(const SegPlan &plan, int32_t n_in, int32_t d_in, int32_t d_out, const int32_t *row_ptr,
+                         const int32_t *col_idx, const float *w_col, const float *row_scale,
+                         const float *H_in, const float *Hu, float *partials, float *A,
+                         const SpmmRowPart &part, const float *W, float *H_out, bool relu,
+                         const Dropout &drop, hipStream_t s);
 // For stacked column u < n_in + *n_kept:  g = sum_{v in t_row u} w_col[v] dA[v,:];
-//   u <  n_in: dH_in[u,:] = row_scale[u] * (init[u,:] + g)  (if mask_src is given: zeroed where
-//              mask_src[u,:] <= 0, multiplied by mask_scale elsewhere)
+//   u <  n_in: dH_in[u,:] = row_scale[u] * (init[u,:] + g)  (zeroed where mask_src[u,:] <= 0 if given)
 //   u >= n_in: dhalo[u-n_in,:] = s_halo * dis_halo[kept_ids[u-n_in]] * g   (skipped if dhalo null)
 // row_scale, dis_halo, init nullable.  plan: segmentation of the transposed inner-inner block.
 hipError_t spmm_bwd(const SegPlan &plan, int32_t n_in, int32_t n_halo, int32_t d,
                     const int32_t *t_row_ptr, const int32_t *t_col_idx, const int32_t *kept_ids,
                     const int32_t *n_kept, const float *w_col, const float *row_scale,
                     const float *dis_halo, float s_halo, const float *dA, const float *mask_src,
-                    float mask_scale, const float *init, bool skip_self, float *partials, float *dH_in,
-                    float *dhalo, hipStream_t s);
+                    const float *init, bool skip_self, float *partials, float *dH_in, float *dhalo,
+                    hipStream_t s);
 
 // ---- gemm.hip (Eq. 2 and its backward; fp32 MFMA) ----------------------------------------------
 // Dropout on a hidden layer's output (training set-up of Section 4): element (row, col) is kept iff
@@ -123,11 +136,10 @@ hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float 
                    bool relu, bool accumulate, const Dropout &drop, hipStream_t s);
 // inv[i] = deg[i] > 1 ? 1 / (deg[i] - 1) : 0   (deg counts the self-loop)
 hipError_t degree_inverse(const int32_t *deg, int32_t n, float *inv, hipStream_t s);
-// C[M,N] = A[M,K] B[N,K]^T.  mask_src (nullable, [M,N]): C is zeroed where mask_src <= 0 and
-// multiplied by mask_scale elsewhere.
+// C[M,N] = alpha * A[M,K] B[N,K]^T.  mask_src (nullable, [M,N]): C is zeroed where mask_src <= 0.
 // m_dev (nullable): device-side row count, *m_dev <= M; rows past it are not touched.
 hipError_t gemm_nt(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   const float *mask_src, float mask_scale, const int32_t *m_dev, hipStream_t s);
+                   const float *mask_src, float alpha, const int32_t *m_dev, hipStream_t s);
 // C[M,N] = A[K,M]^T B[K,N] with K split over the grid; partials: scratch f32[splits*M*N],
 // summed in a fixed order.  splitk_splits() gives the split count used for (M,N,K).
 int32_t splitk_splits(int32_t M, int32_t N, int32_t K);

@@ -14,106 +14,15 @@
 // and handed to the loop by cross-lane reads, four neighbours in flight per step.
 #include <algorithm>
 
-#include "device_utils.hpp"
-#include "kernels.hpp"
+#include "spmm_device.hpp"
 
 namespace bns {
 
-typedef float v2f __attribute__((ext_vector_type(2)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-template <int VEC> struct Vec;
-template <> struct Vec<1> { using T = float; };
-template <> struct Vec<2> { using T = v2f; };
-template <> struct Vec<4> { using T = v4f; };
-
-template <int VEC>
-__device__ __forceinline__ void vec_fma(float (&acc)[VEC], float w, const typename Vec<VEC>::T &v) {
-  const float *p = reinterpret_cast<const float *>(&v);
-#pragma unroll
-  for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, p[i], acc[i]);
-}
-
-struct SpmmArgs {
-  SegPlan plan;                // static segmentation of rows 0..n_split-1
-  const int32_t *n_extra_dev;  // nullable: *n_extra_dev further single-segment rows follow (kept boundary)
-  int32_t d;
-  const int32_t *row_ptr, *col_idx;
-  int32_t n_split;             // columns < n_split read src0 (weight w_col[c]); others src1 (weight 1)
-  const float *src0, *src1, *w_col;
-  float *partials;             // one d-vector per segment of multi-segment rows
-  // output rows < n_split: out0 (scale out_scale0[row], optional mask); others: out1
-  float *out0, *out1;
-  const float *out_scale0;
-  const float *mask_src;
-  float mask_scale;            // factor on the elements that pass the mask
-  const int32_t *kept_ids;     // out1 row r is scaled by s_halo * dis_halo[kept_ids[r]]
-  const float *dis_halo;
-  float s_halo;
-  // optional restriction of rows < n_split to a part of their entries, and an initial value:
-  const int32_t *row_skip;     // skip the first row_skip[row] entries (nullable)
-  const int32_t *row_take;     // then use row_take[row] entries instead of the rest (nullable)
-  const float *init;           // out0 row = scale * (init row + sum) (nullable)
-  bool skip_self;              // entries with column == row contribute nothing (mean aggregator)
-  // feature slicing over the XCDs (n_slices = 1: off).  Workgroups are handed to the 8 XCDs in
-  // turn, so workgroup b runs on XCD b % 8; with n_slices = S that XCD only ever touches the
-  // d_slice = d / S floats of slice (b % 8) % S of every feature row, and its private L2 holds S
-  // times as many distinct rows.
-  int32_t n_slices, d_slice;
-};
-
-// Scale, optional ReLU mask and store of one finished row slice held as acc[c][i].
-template <int VEC, int MAXCH>
-__device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, int nvec, int d_off,
-                                           float (&acc)[MAXCH][VEC]) {
-  using V = typename Vec<VEC>::T;
-  const int d = a.d;
-  float scale;
-  float *out;
-  const float *mask = nullptr;
-  const float *init = nullptr;
-  if (row < a.n_split) {
-    if (a.init) init = a.init + (size_t)row * d + d_off;
-    scale = a.out_scale0 ? a.out_scale0[row] : 1.f;
-    out = a.out0 + (size_t)row * d + d_off;
-    if (a.mask_src) mask = a.mask_src + (size_t)row * d + d_off;
-  } else {
-    if (a.out1 == nullptr) return;
-    const int r = row - a.n_split;
-    scale = a.dis_halo ? a.s_halo * a.dis_halo[a.kept_ids[r]] : a.s_halo;
-    out = a.out1 + (size_t)r * d + d_off;
-  }
-#pragma unroll
-  for (int c = 0; c < MAXCH; ++c) {
-    const int iv = c * kWave + sl;
-    if (iv < nvec) {
-      V o;
-      float *po = reinterpret_cast<float *>(&o);
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) po[i] = acc[c][i];
-      if (init) {
-        const V x0 = reinterpret_cast<const V *>(init)[iv];
-        const float *p0 = reinterpret_cast<const float *>(&x0);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) po[i] += p0[i];
-      }
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) po[i] *= scale;
-      if (mask) {
-        const V m = reinterpret_cast<const V *>(mask)[iv];
-        const float *pm = reinterpret_cast<const float *>(&m);
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) po[i] = pm[i] > 0.f ? po[i] * a.mask_scale : 0.f;
-      }
-      reinterpret_cast<V *>(out)[iv] = o;
-    }
-  }
-}
-
+// Measured on gfx950: the same code runs 3-6 % slower as soon as the wavefront needs more than 96
+// scalar registers (seven 16-register granules instead of six), so the budget is pinned.
 template <int VEC, int MAXCH, int LPR>
-__global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96))) spmm_kernel(const SpmmArgs a) {
   using V = typename Vec<VEC>::T;
-  constexpr int EP = kWave / LPR;  // neighbours walked at once
-  constexpr int UNR = 4;
   const int lane = lane_id();
   const int g = lane / LPR, sl = lane % LPR;
   const int d = a.d;
@@ -127,10 +36,14 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
     nblk = (nblk >> 3) * per;
   }
   // work units: the static segments, then one unit per kept boundary row (count on the device)
-  const int n_units = a.plan.n_seg + (a.n_extra_dev ? *a.n_extra_dev : 0);
+  const int n_units = a.multi_only ? a.plan.n_part : a.plan.n_seg + (a.n_extra_dev ? *a.n_extra_dev : 0);
   for (int unit = bid * 4 + (threadIdx.x >> 6); unit < n_units; unit += nblk * 4) {
   int row, seg = 0, nseg = 1;
-  if (unit < a.plan.n_seg) {
+  if (a.multi_only) {  // units are the partial-sum slots, i.e. the segments of the long rows
+    row = a.plan.part_row[unit];
+    seg = unit - a.plan.part_ptr[row];
+    nseg = a.plan.seg_ptr[row + 1] - a.plan.seg_ptr[row];
+  } else if (unit < a.plan.n_seg) {
     row = a.plan.seg_row[unit];
     const int s0 = a.plan.seg_ptr[row];
     seg = unit - s0;
@@ -150,69 +63,7 @@ __global__ void __launch_bounds__(256) spmm_kernel(const SpmmArgs a) {
   }
 
   float acc[MAXCH][VEC];
-#pragma unroll
-  for (int c = 0; c < MAXCH; ++c)
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) acc[c][i] = 0.f;
-
-  for (int base = e0; base < e1; base += kWave) {
-    const int cnt = min(kWave, e1 - base);
-    // one neighbour per lane: its feature-row address and weight
-    unsigned long long p_l = 0;
-    float w_l = 0.f;
-    if (lane < cnt) {
-      const int c = a.col_idx[base + lane];
-      if (c < a.n_split) {
-        p_l = (unsigned long long)(a.src0 + (size_t)c * d + d_off);
-        w_l = a.w_col ? a.w_col[c] : 1.f;
-        if (a.skip_self && c == row) w_l = 0.f;  // the stored self-loop is not a neighbour
-      } else {
-        p_l = (unsigned long long)(a.src1 + (size_t)(c - a.n_split) * d + d_off);
-        w_l = 1.f;
-      }
-    }
-    const unsigned p_lo = (unsigned)p_l, p_hi = (unsigned)(p_l >> 32);
-    for (int j = 0; j < cnt; j += UNR * EP) {
-      V v[UNR][MAXCH];
-      float w[UNR];
-#pragma unroll
-      for (int t = 0; t < UNR; ++t) {
-        const int jj = j + t * EP + g;
-        const bool valid = jj < cnt;
-        unsigned lo, hi;
-        float wt;
-        if constexpr (EP == 1) {  // jj is uniform over the wavefront
-          const int js = __builtin_amdgcn_readfirstlane(jj) & (kWave - 1);
-          lo = __builtin_amdgcn_readlane(p_lo, js);
-          hi = __builtin_amdgcn_readlane(p_hi, js);
-          wt = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w_l), js));
-        } else {
-          lo = __shfl(p_lo, jj & (kWave - 1), kWave);
-          hi = __shfl(p_hi, jj & (kWave - 1), kWave);
-          wt = __shfl(w_l, jj & (kWave - 1), kWave);
-        }
-        w[t] = valid ? wt : 0.f;
-        const V *src = reinterpret_cast<const V *>(((unsigned long long)hi << 32) | lo);
-#pragma unroll
-        for (int c = 0; c < MAXCH; ++c) {
-          const int iv = c * kWave + sl;
-          if (valid && iv < nvec) v[t][c] = src[iv];
-          else v[t][c] = V{};
-        }
-      }
-#pragma unroll
-      for (int t = 0; t < UNR; ++t)
-#pragma unroll
-        for (int c = 0; c < MAXCH; ++c) vec_fma<VEC>(acc[c], w[t], v[t][c]);
-    }
-  }
-
-  if constexpr (EP > 1) {
-#pragma unroll
-    for (int off = LPR; off < kWave; off <<= 1)
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) acc[0][i] += __shfl_xor(acc[0][i], off, kWave);
-  }
+  gather_segment<VEC, MAXCH, LPR>(a, row, e0, e1, d_off, nvec, acc);
 
   if (g != 0) {
     // only the first lane group holds the folded sums
@@ -283,7 +134,7 @@ static hipError_t launch_spmm_vec(const SpmmArgs &a_in, int64_t max_units, hipSt
   // Wide rows are cut into slices of 128 floats (64 where rows are long enough to keep a
   // wavefront busy with a quarter of its lanes per neighbour); measured on the five workloads,
   // narrower slices lose more to the repeated index walk than the L2 gains.
-  if (VEC == 4) {
+  if (VEC == 4 && !a.multi_only) {
     const int target = a.plan.avg_len >= 64 ? 64 : 128;
     int S = 1;
     while (S < 8 && a.d / (2 * S) >= target && a.d % (2 * S * VEC) == 0) S *= 2;
@@ -298,6 +149,7 @@ static hipError_t launch_spmm_vec(const SpmmArgs &a_in, int64_t max_units, hipSt
   const int64_t seg_blocks = ((int64_t)a.plan.n_seg + 3) / 4;
   const int64_t extra_blocks = std::min<int64_t>((max_units - a.plan.n_seg + 3) / 4, 8192);
   unsigned blocks = (unsigned)(seg_blocks + std::max<int64_t>(extra_blocks, 0));
+  if (a.multi_only) blocks = (unsigned)((a.plan.n_part + 3) / 4);
   const unsigned cblocks = (unsigned)((a.plan.n_multi + 3) / 4);
   if (blocks == 0) return hipSuccess;
   if (a.n_slices > 1) {
@@ -339,15 +191,9 @@ static hipError_t launch_spmm(const SpmmArgs &a, int64_t max_units, hipStream_t 
 hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
                     const int32_t *col_idx, const float *w_col, const float *row_scale,
                     const float *H_in, const float *Hu, float *partials, float *A,
-                    const SpmmRowPart &part, hipStream_t s) {
-  SpmmArgs a{};
-  a.plan = plan; a.n_extra_dev = nullptr; a.d = d;
-  a.row_ptr = row_ptr; a.col_idx = col_idx; a.n_split = n_in;
-  a.src0 = H_in; a.src1 = Hu; a.w_col = w_col; a.partials = partials;
-  a.out0 = A; a.out1 = nullptr; a.out_scale0 = row_scale; a.mask_src = nullptr; a.mask_scale = 1.f;
-  a.kept_ids = nullptr; a.dis_halo = nullptr; a.s_halo = 0.f;
-  a.row_skip = part.row_skip; a.row_take = part.row_take; a.init = part.init;
-  a.skip_self = part.skip_self;
+                    const SpmmRowPart &part, bool long_rows_only, hipStream_t s) {
+  SpmmArgs a = spmm_fwd_args(plan, n_in, d, row_ptr, col_idx, w_col, row_scale, H_in, Hu, partials, A, part);
+  a.multi_only = long_rows_only;
   return launch_spmm(a, plan.n_seg, s);
 }
 
@@ -355,15 +201,14 @@ hipError_t spmm_bwd(const SegPlan &plan, int32_t n_in, int32_t n_halo, int32_t d
                     const int32_t *t_row_ptr, const int32_t *t_col_idx, const int32_t *kept_ids,
                     const int32_t *n_kept, const float *w_col, const float *row_scale,
                     const float *dis_halo, float s_halo, const float *dA, const float *mask_src,
-                    float mask_scale, const float *init, bool skip_self, float *partials, float *dH_in,
-                    float *dhalo, hipStream_t s) {
+                    const float *init, bool skip_self, float *partials, float *dH_in, float *dhalo,
+                    hipStream_t s) {
   SpmmArgs a{};
   const bool halo_rows = dhalo && n_halo > 0;
   a.plan = plan; a.n_extra_dev = halo_rows ? n_kept : nullptr; a.d = d;
   a.row_ptr = t_row_ptr; a.col_idx = t_col_idx; a.n_split = n_in;
   a.src0 = dA; a.src1 = nullptr; a.w_col = w_col; a.partials = partials;
   a.out0 = dH_in; a.out1 = dhalo; a.out_scale0 = row_scale; a.mask_src = mask_src;
-  a.mask_scale = mask_scale;
   a.kept_ids = kept_ids; a.dis_halo = dis_halo; a.s_halo = s_halo;
   a.init = init; a.skip_self = skip_self;
   return launch_spmm(a, (int64_t)plan.n_seg + (halo_rows ? n_halo : 0), s);
@@ -390,12 +235,16 @@ seg_multi_kernel(int32_t n_rows, const int32_t *__restrict__ seg_ptr, int which,
 
 __global__ void __launch_bounds__(256)
 seg_fill_kernel(int32_t n_rows, const int32_t *__restrict__ seg_ptr, const int32_t *__restrict__ mpos,
-                int32_t *__restrict__ seg_row, int32_t *__restrict__ mrow) {
+                const int32_t *__restrict__ part_ptr, int32_t *__restrict__ seg_row,
+                int32_t *__restrict__ mrow, int32_t *__restrict__ part_row) {
   const int v = blockIdx.x * 256 + threadIdx.x;
   if (v >= n_rows) return;
   const int s0 = seg_ptr[v], s1 = seg_ptr[v + 1];
   for (int s = s0; s < s1; ++s) seg_row[s] = v;
-  if (s1 - s0 > 1) mrow[mpos[v]] = v;
+  if (s1 - s0 > 1) {
+    mrow[mpos[v]] = v;
+    for (int s = 0; s < s1 - s0; ++s) part_row[part_ptr[v] + s] = v;
+  }
 }
 
 hipError_t build_seg_plan(int32_t n_rows, int64_t nnz, const int32_t *row_ptr, SegPlan *plan, int32_t *tmp_a,
@@ -410,7 +259,8 @@ hipError_t build_seg_plan(int32_t n_rows, int64_t nnz, const int32_t *row_ptr, S
   seg_multi_kernel<<<blocks, 256, 0, s>>>(n_rows, plan->seg_ptr, 1, tmp_a);
   e = scan_exclusive_i32(tmp_a, tmp_b, n_rows, nullptr, tile_sums, nullptr, 0, s);
   if (e != hipSuccess) return e;
-  seg_fill_kernel<<<blocks, 256, 0, s>>>(n_rows, plan->seg_ptr, tmp_b, plan->seg_row, plan->mrow);
+  seg_fill_kernel<<<blocks, 256, 0, s>>>(n_rows, plan->seg_ptr, tmp_b, plan->part_ptr, plan->seg_row, plan->mrow,
+                                         plan->part_row);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   // the three totals size the launches: bring them to the host (set-up only)

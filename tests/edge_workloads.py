@@ -45,6 +45,15 @@ def star():
     return _finish("edge-star", part, [7, 5, 3], 0, 12)
 
 
+def star_wide():
+    """The star graph again with widths between 65 and 128 that are multiples of 4: the layers that
+    aggregate and update in one kernel.  The hub row (3000 entries) is finished by the segmented
+    pass and read back; 3000 rows leave a ragged last tile of 56; 72 and 100 need depth padding."""
+    w = star()
+    dims = [72, 100, 128, 5]
+    return _finish("edge-star-wide", w.part, dims, 0, 16)
+
+
 def single_node():
     """|V| = 1 with two boundary neighbours; widths 1 and 2; multi-label loss."""
     part = partition_from_entries(0, 1, np.zeros(0, np.int64), np.zeros(0, np.int64),
@@ -68,4 +77,4 @@ def wide_odd():
     return _finish("edge-wide-odd", part, [602, 130, 66, 9], 0, 15)
 
 
-EDGE = {"e-nobd": no_boundary, "e-star": star, "e-single": single_node, "e-wide": wide_odd}
+EDGE = {"e-nobd": no_boundary, "e-star": star, "e-starw": star_wide, "e-single": single_node, "e-wide": wide_odd}
