@@ -129,8 +129,12 @@ def main():
         fwd_bytes += -(4 * nnz + 4 * dims[0] * (n_in + n_kept)) + 4 * e_u + 4 * dims[0] * (n_in + n_kept)
     bwd_bytes = sum(4 * nnz + 4 * (n_in + n_kept + 1) + 4 * dims[l - 1] * n_in
                     + 4 * dims[l - 1] * (n_in + n_kept) for l in range(2, L + 1))
+    # layers whose forward aggregate and update run as one kernel: their update is timed (and counted)
+    # with the aggregate; it also writes H_out and reads W there, and A is not read back
+    fused = [l for l in range(1, L + 1) if ctx.layer_is_fused(l)]
+    fwd_bytes += sum(4 * n_in * dims[l] + 4 * dims[l - 1] * dims[l] for l in fused)
     kw = 2 if kind == 1 else 1      # the concat update doubles the depth of every product
-    gemm_flops = {"gemm_fwd": sum(2 * kw * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1)),
+    gemm_flops = {"gemm_fwd": sum(2 * kw * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1) if l not in fused),
                   "gemm_dw": sum(2 * kw * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1)),
                   "gemm_da": sum(2 * kw * n_in * dims[l - 1] * dims[l] for l in range(2, L + 1))}
     per_step_ms = {k: v[0] / args.steps for k, v in phases.items()}
@@ -156,7 +160,7 @@ def main():
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
             tr = json.load(fh)
         if tr["workload"].startswith(f"config {w.cfg}:") and abs(tr["p"] - p) < 1e-12:
-            roof["traffic"] = tr["bytes_per_launch"].get(dom.split("_")[0])
+            roof["traffic"] = tr["bytes_per_launch"].get(dom)
             roof["traffic_source"] = tr["source"]
     except (OSError, KeyError, ValueError):
         pass
@@ -168,12 +172,13 @@ def main():
         classes[k + "_TFLOPs"] = fl / (per_step_ms[k] * 1e-3) / 1e12 if per_step_ms[k] else None
 
     # ---- whole-step roofline: sum over kernel classes of max(compulsory bytes / HBM peak, flops / MFMA peak)
-    gemm_bytes = {"gemm_fwd": sum(4 * n_in * (kw * dims[l - 1] + dims[l]) for l in range(1, L + 1)),
+    gemm_bytes = {"gemm_fwd": sum(4 * n_in * (kw * dims[l - 1] + dims[l]) for l in range(1, L + 1) if l not in fused),
                   "gemm_dw": sum(4 * n_in * (kw * dims[l - 1] + dims[l]) for l in range(1, L + 1)),
                   "gemm_da": sum(4 * n_in * (kw * dims[l - 1] + dims[l]) for l in range(2, L + 1))}
     t_roof = (fwd_bytes + bwd_bytes) / (HBM_PEAK_GBS * 1e9)
     t_roof += sum(max(gemm_flops[k] / (FP32_MFMA_PEAK_TFLOPS * 1e12), gemm_bytes[k] / (HBM_PEAK_GBS * 1e9))
                   for k in gemm_flops)
+    t_roof += sum(2 * n_in * dims[l - 1] * dims[l] for l in fused) / (FP32_MFMA_PEAK_TFLOPS * 1e12)  # fused updates
     t_roof += sum(8 * n_kept * dims[l - 1] for l in range(1, L + 1)) / (HBM_PEAK_GBS * 1e9)      # halo gather
     t_roof += 8 * n_in * dims[L] / (HBM_PEAK_GBS * 1e9)                                          # loss
     t_roof += (12 * P.n_halo + 4 * n_kept + 8 * P.e_bd + 8 * nnz + 8 * (n_in + 1)) / (HBM_PEAK_GBS * 1e9)  # sample + CSRs
@@ -208,7 +213,8 @@ def main():
                    "loss": "softmax_ce" if w.loss_kind == 0 else "sigmoid_bce",
                    "edges_per_step": edges_per_step, "setup_s": round(t_setup, 1),
                    "input_aggregate_cached": not args.no_input_cache,
-                   "layer": "gcn" if kind == 0 else "graphsage-mean", "dropout": args.dropout},
+                   "layer": "gcn" if kind == 0 else "graphsage-mean", "dropout": args.dropout,
+                   "fused_aggregate_update_layers": fused},
         "roofline": roof,
         "phases_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
         "kernel_classes": classes,

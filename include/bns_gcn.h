@@ -173,6 +173,13 @@ bns_status bns_graph_capture(bns_ctx *ctx, uint64_t seed, uint32_t first_epoch, 
                              void *stream);
 bns_status bns_graph_replay(bns_ctx *ctx, int32_t n_epochs, void *stream);
 
+/* 1 if the forward pass of `layer` (1..L) runs aggregate and update (Eq. 1 and Eq. 2) in one
+ * kernel, 0 if it runs them as two.  One kernel is used for the GCN layer when the layer's input
+ * width is a multiple of 4 between 68 and 128; results are the same to rounding, only the kernel
+ * boundaries (and what the phase timers attribute to BNS_PHASE_SPMM_FWD / BNS_PHASE_GEMM_FWD)
+ * differ.  Host-only query, never fails. */
+int32_t bns_layer_is_fused(const bns_ctx *ctx, int32_t layer);
+
 /* Dropout on the hidden activations, as in the training set-up of Section 4 (rates 0.1 - 0.5).
  * With rate q in (0, 1) every element of the output of a layer that has a ReLU (layers 1..L-1 of
  * bns_train_step, relu != 0 in bns_gcn_layer_fwd) is zeroed with probability q and multiplied by

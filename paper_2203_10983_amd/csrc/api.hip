@@ -568,6 +568,11 @@ bns_status bns_graph_replay(bns_ctx *ctx, int32_t n_epochs, void *stream) {
   return BNS_OK;
 }
 
+int32_t bns_layer_is_fused(const bns_ctx *ctx, int32_t layer) {
+  if (!ctx || layer < 1 || layer >= (int32_t)ctx->dims.size()) return 0;
+  return ctx->layer_kind == 0 && spmm_gemm_fwd_supported(ctx->dims[layer - 1]) ? 1 : 0;
+}
+
 bns_status bns_set_dropout(bns_ctx *ctx, double q) {
   if (!ctx) return BNS_EINVAL;
   if (!(q >= 0.0 && q < 1.0)) return fail(ctx, BNS_EINVAL, "dropout rate must lie in [0, 1)");

@@ -132,8 +132,7 @@ __global__ void __launch_bounds__(kFThreads, 6) __attribute__((amdgpu_num_sgpr(9
   }
   // ---- phase 2: H_out tile = A tile x W ----------------------------------------------------------
   // W comes from L2 in 16-row pieces, each requested one step ahead (the first one before the
-  // barrier that ends the gather) and passed through a double-buffered LDS tile; with 8 steps per
-  // column tile the buffer parity carries over from one tile to the next.
+  // barrier that ends the gather) and passed through a double-buffered LDS tile.
   const int wm = (wid >> 2) * 32, wn = (wid & 3) * 32;
   const int l32 = lane & 31, lhi = lane >> 5;
   const int N = f.d_out;
@@ -156,23 +155,27 @@ __global__ void __launch_bounds__(kFThreads, 6) __attribute__((amdgpu_num_sgpr(9
     }
     return v;
   };
-  float4 wv = load_w(0, 0);  // in flight across the barrier
+  float4 wv = load_w(0, 0);  // in flight across the barrier that ends the gather
   __syncthreads();
   for (int n0 = 0; n0 < N; n0 += kFBn) {
     floatx16 acc;
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    *reinterpret_cast<float4 *>(&Bs[0][bk * kFLdb + bq]) = wv;
+    __syncthreads();
+#pragma unroll 1
     for (int kt = 0; kt < nk; ++kt) {
       const int buf = kt & 1;
-      *reinterpret_cast<float4 *>(&Bs[buf][bk * kFLdb + bq]) = wv;
-      // next piece: the following depth step, or the first one of the next column tile
+      // request the next piece (next depth step, or the first one of the next column tile), issue
+      // this step's products, and only then wait for the piece and stage it
       wv = kt + 1 < nk ? load_w(n0, (kt + 1) * kFBk) : load_w(n0 + kFBn, 0);
-      __syncthreads();
       const float *as = As + (wm + l32) * kFLda + kt * kFBk + lhi;
       const float *bs = Bs[buf] + lhi * kFLdb + wn + l32;
 #pragma unroll
       for (int kk = 0; kk < kFBk; kk += 2)
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(as[kk], bs[kk * kFLdb], acc, 0, 0, 0);
+      if (kt + 1 < nk) *reinterpret_cast<float4 *>(&Bs[buf ^ 1][bk * kFLdb + bq]) = wv;
+      __syncthreads();
     }
     // C element of (lane, register r): row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32
     const int col = n0 + wn + l32;
