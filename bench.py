@@ -121,17 +121,21 @@ def main():
 
     # ---- roofline of the dominant kernel class --------------------------------------------------
     n_in, dims = P.n_in, w.dims
-    fwd_bytes = sum(4 * nnz + 4 * (n_in + 1) + 4 * dims[l - 1] * (n_in + n_kept) + 4 * dims[l - 1] * n_in
+    # how train_step runs each layer: one kernel for aggregate + update (its update is timed and counted
+    # with the aggregate: it also writes H_out and reads W there, and A is not read back), or update
+    # first (the aggregate then runs at the output width)
+    fused = [l for l in range(1, L + 1) if ctx.layer_plan(l) == pkg.LAYER_ONE_KERNEL]
+    first = [l for l in range(1, L + 1) if ctx.layer_plan(l) == pkg.LAYER_UPDATE_FIRST]
+    fw = {l: dims[l] if l in first else dims[l - 1] for l in range(1, L + 1)}        # forward aggregate width
+    bw = {l: dims[l] if (kind == 0 and dims[l] < dims[l - 1]) else dims[l - 1] for l in range(2, L + 1)}
+    fwd_bytes = sum(4 * nnz + 4 * (n_in + 1) + 4 * fw[l] * (n_in + n_kept) + 4 * fw[l] * n_in
                     for l in range(1, L + 1))
     if not args.no_input_cache:
         # layer 1 reads the cached inner sum and the kept boundary rows instead of all neighbours
         e_u = nnz - P.e_in
         fwd_bytes += -(4 * nnz + 4 * dims[0] * (n_in + n_kept)) + 4 * e_u + 4 * dims[0] * (n_in + n_kept)
-    bwd_bytes = sum(4 * nnz + 4 * (n_in + n_kept + 1) + 4 * dims[l - 1] * n_in
-                    + 4 * dims[l - 1] * (n_in + n_kept) for l in range(2, L + 1))
-    # layers whose forward aggregate and update run as one kernel: their update is timed (and counted)
-    # with the aggregate; it also writes H_out and reads W there, and A is not read back
-    fused = [l for l in range(1, L + 1) if ctx.layer_is_fused(l)]
+    bwd_bytes = sum(4 * nnz + 4 * (n_in + n_kept + 1) + 4 * bw[l] * n_in
+                    + 4 * bw[l] * (n_in + n_kept) for l in range(2, L + 1))
     fwd_bytes += sum(4 * n_in * dims[l] + 4 * dims[l - 1] * dims[l] for l in fused)
     kw = 2 if kind == 1 else 1      # the concat update doubles the depth of every product
     gemm_flops = {"gemm_fwd": sum(2 * kw * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1) if l not in fused),
@@ -214,7 +218,7 @@ def main():
                    "edges_per_step": edges_per_step, "setup_s": round(t_setup, 1),
                    "input_aggregate_cached": not args.no_input_cache,
                    "layer": "gcn" if kind == 0 else "graphsage-mean", "dropout": args.dropout,
-                   "fused_aggregate_update_layers": fused},
+                   "one_kernel_layers": fused, "update_first_layers": first},
         "roofline": roof,
         "phases_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
         "kernel_classes": classes,

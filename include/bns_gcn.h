@@ -173,12 +173,22 @@ bns_status bns_graph_capture(bns_ctx *ctx, uint64_t seed, uint32_t first_epoch, 
                              void *stream);
 bns_status bns_graph_replay(bns_ctx *ctx, int32_t n_epochs, void *stream);
 
-/* 1 if the forward pass of `layer` (1..L) runs aggregate and update (Eq. 1 and Eq. 2) in one
- * kernel, 0 if it runs them as two.  One kernel is used for the GCN layer when the layer's input
- * width is a multiple of 4 between 68 and 128; results are the same to rounding, only the kernel
- * boundaries (and what the phase timers attribute to BNS_PHASE_SPMM_FWD / BNS_PHASE_GEMM_FWD)
- * differ.  Host-only query, never fails. */
-int32_t bns_layer_is_fused(const bns_ctx *ctx, int32_t layer);
+/* How bns_train_step runs layer `layer` (1..L); host-only query, -1 for a bad argument.  The
+ * three plans give the same results up to rounding (Appendix A writes Z = P H W without
+ * parentheses); they differ in kernel boundaries, in what BNS_VIEW_A holds and in what the phase
+ * timers attribute to BNS_PHASE_SPMM_FWD / BNS_PHASE_GEMM_FWD.
+ *   BNS_LAYER_TWO_KERNELS  aggregate (Eq. 1), then update (Eq. 2); BNS_VIEW_A = the aggregate.
+ *   BNS_LAYER_ONE_KERNEL   the same two steps in one kernel (GCN layer, input width a multiple of
+ *                          4 between 68 and 128); BNS_VIEW_A = the aggregate.
+ *   BNS_LAYER_UPDATE_FIRST a GCN layer whose output is at most 3/4 as wide as its input (and whose
+ *                          aggregate thereby gathers at least 2^24 fewer floats) is run as
+ *                          P (H W): the products H W and H_U W first, then the aggregate at the
+ *                          output width; its backward pass forms the weight gradient as
+ *                          [H ; H_U]^T (P^T dZ).  BNS_VIEW_A then holds H W (n_in x d_l).  Not
+ *                          used for layer 1 while bns_cache_input_aggregate is in effect.
+ * bns_gcn_layer_fwd / bns_gcn_layer_bwd always aggregate first (their A_saved is the aggregate). */
+typedef enum { BNS_LAYER_TWO_KERNELS = 0, BNS_LAYER_ONE_KERNEL = 1, BNS_LAYER_UPDATE_FIRST = 2 } bns_layer_plan_kind;
+int32_t bns_layer_plan(const bns_ctx *ctx, int32_t layer);
 
 /* Dropout on the hidden activations, as in the training set-up of Section 4 (rates 0.1 - 0.5).
  * With rate q in (0, 1) every element of the output of a layer that has a ReLU (layers 1..L-1 of

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libbns_gcn.so")
 
 EXPORTED = ["bns_workspace_bytes", "bns_create", "bns_destroy", "bns_last_error",
             "bns_sample_boundary", "bns_build_sampled_csr", "bns_gcn_layer_fwd",
-            "bns_gcn_layer_bwd", "bns_train_step", "bns_graph_capture", "bns_graph_replay", "bns_set_dropout", "bns_layer_is_fused", "bns_adam_update", "bns_cache_input_aggregate", "bns_ws_view",
+            "bns_gcn_layer_bwd", "bns_train_step", "bns_graph_capture", "bns_graph_replay", "bns_set_dropout", "bns_layer_plan", "bns_adam_update", "bns_cache_input_aggregate", "bns_ws_view",
             "bns_profile_enable", "bns_profile_read"]
 
 PHASES = ["sample", "build", "gather", "spmm_fwd", "gemm_fwd", "loss", "gemm_dw", "gemm_da",
@@ -25,6 +25,7 @@ PHASES = ["sample", "build", "gather", "spmm_fwd", "gemm_fwd", "loss", "gemm_dw"
 
 VIEW_KEPT_IDS, VIEW_REMAP, VIEW_N_KEPT, VIEW_ROW_PTR, VIEW_COL_IDX = 0, 1, 2, 3, 4
 VIEW_T_ROW_PTR, VIEW_T_COL_IDX, VIEW_NNZ, VIEW_A, VIEW_H = 5, 6, 7, 8, 9
+LAYER_TWO_KERNELS, LAYER_ONE_KERNEL, LAYER_UPDATE_FIRST = 0, 1, 2
 
 _STATUS = {0: "BNS_OK", 1: "BNS_EINVAL", 2: "BNS_EOVERFLOW", 3: "BNS_EWORKSPACE", 4: "BNS_EHIP"}
 
@@ -86,8 +87,8 @@ def load_library():
     L.bns_graph_capture.argtypes = L.bns_train_step.argtypes
     L.bns_graph_replay.restype = i32
     L.bns_graph_replay.argtypes = [vp, i32, vp]
-    L.bns_layer_is_fused.restype = i32
-    L.bns_layer_is_fused.argtypes = [vp, i32]
+    L.bns_layer_plan.restype = i32
+    L.bns_layer_plan.argtypes = [vp, i32]
     L.bns_set_dropout.restype = i32
     L.bns_set_dropout.argtypes = [vp, C.c_double]
     L.bns_adam_update.restype = i32
@@ -211,8 +212,9 @@ class Context:
     def graph_replay(self, n_epochs):
         self._check(self._lib.bns_graph_replay(self._ctx, n_epochs, _stream()))
 
-    def layer_is_fused(self, layer):
-        return bool(self._lib.bns_layer_is_fused(self._ctx, layer))
+    def layer_plan(self, layer):
+        """LAYER_TWO_KERNELS / LAYER_ONE_KERNEL / LAYER_UPDATE_FIRST: how train_step runs the layer."""
+        return int(self._lib.bns_layer_plan(self._ctx, layer))
 
     def set_dropout(self, q):
         self._check(self._lib.bns_set_dropout(self._ctx, float(q)))

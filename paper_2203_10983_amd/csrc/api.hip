@@ -39,7 +39,7 @@ struct Layout {
   int32_t *tile_sums;
   uint64_t *ballots;
   int32_t *kpos, *hlen;
-  float *Hu, *G0, *G1, *G2, *partials, *loss_partials;
+  float *Hu, *Hu2, *G0, *G1, *G2, *partials, *loss_partials;  // Hu2: boundary rows at the output width
   float *inv_deg;            // 1 / (full-graph degree) of the inner nodes, for the mean aggregator
   SegPlan plan_f, plan_b;   // segmentation of the static CSR and of the transposed inner block
   int32_t *seg_tmp_a, *seg_tmp_b;
@@ -86,6 +86,12 @@ struct bns_ctx {
 
 namespace {
 
+// A GCN layer that shrinks its width by a quarter or more is run update first in bns_train_step:
+// (P (H W)) instead of ((P H) W), so that the aggregate moves d_out instead of d_in floats per entry.
+bool update_first_shape(int layer_kind, int d_in, int d_out) {
+  return layer_kind == 0 && (int64_t)d_out * 4 <= (int64_t)d_in * 3;
+}
+
 bool valid_desc(const bns_partition_desc *p, const bns_model_desc *m) {
   if (!p || !m || !m->dims) return false;
   if (p->n_in < 1 || p->n_halo < 0 || p->nnz0 < p->n_in || p->e_in < p->n_in || p->e_bd < 0) return false;
@@ -107,12 +113,17 @@ bool fits_int32(const bns_partition_desc *p, const bns_model_desc *m) {
 
 size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, Layout *out) {
   const size_t n_in = p->n_in, B = p->n_halo, L = m->n_layers;
-  size_t d_in_max = 0, d_max = 0, part_max = 0;
+  size_t d_in_max = 0, d_max = 0, part_max = 0, d_first_max = 0;
   for (size_t l = 0; l <= L; ++l) d_max = std::max<size_t>(d_max, m->dims[l]);
   for (size_t l = 0; l < L; ++l) {
     d_in_max = std::max<size_t>(d_in_max, m->dims[l]);
     const size_t mn = (size_t)m->dims[l] * m->dims[l + 1];
     part_max = std::max(part_max, mn * (size_t)splitk_splits(m->dims[l], m->dims[l + 1], p->n_in));
+    if (update_first_shape(m->layer_kind, m->dims[l], m->dims[l + 1])) {
+      d_first_max = std::max<size_t>(d_first_max, m->dims[l + 1]);
+      if (p->n_halo > 0)
+        part_max = std::max(part_max, mn * (size_t)splitk_splits(m->dims[l], m->dims[l + 1], p->n_halo));
+    }
   }
   Layout w;
   w.dis_in = c.take<float>(n_in);
@@ -129,6 +140,7 @@ size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, La
   w.kpos = c.take<int32_t>(p->e_bd + 1);
   w.hlen = c.take<int32_t>(B + 1);
   w.Hu = c.take<float>(B * d_in_max);
+  w.Hu2 = c.take<float>(B * d_first_max);
   w.G0 = c.take<float>(n_in * d_max);
   w.G1 = c.take<float>(n_in * d_max);
   w.G2 = c.take<float>(n_in * d_max);
@@ -220,11 +232,47 @@ float mask_scale_of(const bns_ctx *ctx) {
   return ctx->drop_q > 0.0 ? (float)(1.0 / (1.0 - ctx->drop_q)) : 1.f;
 }
 
+// update_first: H_out = act(P [H_in W ; Hu W]) instead of act((P [H_in ; Hu]) W); A_saved then
+// receives H_in W (the aggregate of the inputs is never formed).
+// How bns_train_step runs the forward pass of `layer` when its first-layer input is X.
+int layer_plan(const bns_ctx *ctx, int layer, const float *X) {
+  const int d_in = ctx->dims[layer - 1], d_out = ctx->dims[layer];
+  const bool cached = layer == 1 && ctx->cache_X != nullptr && ctx->cache_X == X;
+  // worth its extra launches only when the aggregate is big: at least 2^24 fewer floats gathered
+  const bool big = (int64_t)ctx->part.nnz0 * (d_in - d_out) >= ((int64_t)1 << 24);
+  if (!cached && big && update_first_shape(ctx->layer_kind, d_in, d_out)) return BNS_LAYER_UPDATE_FIRST;
+  if (ctx->layer_kind == 0 && spmm_gemm_fwd_supported(d_in)) return BNS_LAYER_ONE_KERNEL;
+  return BNS_LAYER_TWO_KERNELS;
+}
+
+// update_first: H_out = act(P [H_in W ; Hu W]) instead of act((P [H_in ; Hu]) W); A_saved then
+// receives H_in W (the aggregate of the inputs is never formed).
 bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, const float *halo_h,
-                          const float *W, float *A_saved, float *H_out, bool relu, hipStream_t s) {
+                          const float *W, float *A_saved, float *H_out, bool relu, bool update_first,
+                          hipStream_t s) {
   const int n_in = ctx->part.n_in, B = ctx->part.n_halo;
   const int d_in = ctx->dims[layer - 1], d_out = ctx->dims[layer];
   const bool sage = ctx->layer_kind == 1;
+  if (update_first) {
+    {
+      PhaseTimer t(ctx, BNS_PHASE_GATHER, s);
+      BNS_TRY("halo_gather", halo_gather(halo_h, ctx->cur_kept, ctx->cur_n_kept, B, ctx->ws.dis_halo, halo_scale(p),
+                                         d_in, ctx->ws.Hu, s));
+    }
+    {
+      PhaseTimer t(ctx, BNS_PHASE_GEMM_FWD, s);
+      BNS_TRY("gemm_nn(inner)", gemm_nn(n_in, d_out, d_in, H_in, W, A_saved, false, false, Dropout{}, nullptr, s));
+      if (B > 0)
+        BNS_TRY("gemm_nn(boundary)", gemm_nn(B, d_out, d_in, ctx->ws.Hu, W, ctx->ws.Hu2, false, false, Dropout{},
+                                             ctx->cur_n_kept, s));
+    }
+    PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
+    BNS_TRY("spmm_fwd", spmm_fwd(ctx->ws.plan_f, n_in, d_out, ctx->cur_row_ptr, ctx->cur_col_idx, ctx->ws.dis_in,
+                                 ctx->ws.dis_in, A_saved, ctx->ws.Hu2, ctx->ws.spmm_partials, H_out, SpmmRowPart{},
+                                 false, relu, s));
+    BNS_TRY("dropout_inplace", dropout_inplace(n_in, d_out, H_out, dropout_of(ctx, layer, relu), s));
+    return BNS_OK;
+  }
   {
     // GCN: rows pre-scaled by (1/p) d~^-1/2; mean aggregator: by 1/p only
     PhaseTimer t(ctx, BNS_PHASE_GATHER, s);
@@ -246,7 +294,7 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
     PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
     BNS_TRY("spmm_fwd(long rows)", spmm_fwd(ctx->ws.plan_f, n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx, w_col,
                                             row_scale, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part,
-                                            true, s));
+                                            true, false, s));
     BNS_TRY("spmm_gemm_fwd", spmm_gemm_fwd(ctx->ws.plan_f, n_in, d_in, d_out, ctx->cur_row_ptr, ctx->cur_col_idx,
                                            w_col, row_scale, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved,
                                            part, W, H_out, relu, dropout_of(ctx, layer, relu), s));
@@ -255,16 +303,17 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
   {
     PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
     BNS_TRY("spmm_fwd", spmm_fwd(ctx->ws.plan_f, n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx, w_col, row_scale,
-                                 H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part, false, s));
+                                 H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part, false, false, s));
   }
   {
     PhaseTimer t(ctx, BNS_PHASE_GEMM_FWD, s);
     if (!sage) {
-      BNS_TRY("gemm_nn", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, relu, false, dropout_of(ctx, layer, relu), s));
+      BNS_TRY("gemm_nn", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, relu, false, dropout_of(ctx, layer, relu),
+                                 nullptr, s));
     } else {  // [z | h] [W_n ; W_s] = z W_n + h W_s
-      BNS_TRY("gemm_nn(nbr)", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, false, false, Dropout{}, s));
+      BNS_TRY("gemm_nn(nbr)", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, false, false, Dropout{}, nullptr, s));
       BNS_TRY("gemm_nn(self)", gemm_nn(n_in, d_out, d_in, H_in, W + (size_t)d_in * d_out, H_out, relu, true,
-                                       dropout_of(ctx, layer, relu), s));
+                                       dropout_of(ctx, layer, relu), nullptr, s));
     }
   }
   return BNS_OK;
@@ -273,11 +322,44 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
 // dZ is the gradient of the layer's pre-activation.  mask_src (nullable): activations of the
 // layer below; when given, dH_in receives the masked gradient (= dZ of the layer below).
 // H_in is needed by the mean-aggregator layer only (its self half of the weight gradient).
+// halo_first (nullable): the boundary features of an update-first layer (A_saved does not hold
+// the aggregate then); the weight gradient is [H_in ; Hu]^T (P^T dZ) instead of A^T dZ.
 bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, const float *A_saved,
                           const float *H_in, const float *W, float *dW, float *dH_in, float *dhalo,
-                          const float *mask_src, hipStream_t s) {
+                          const float *mask_src, bool update_first, const float *halo_first, hipStream_t s) {
   const int n_in = ctx->part.n_in, B = ctx->part.n_halo;
   const int d_in = ctx->dims[layer - 1], d_out = ctx->dims[layer];
+  if (update_first) {
+    float *G_in = ctx->ws.G1, *G_halo = B > 0 ? ctx->ws.Hu2 : nullptr;
+    {  // G = P^T dZ at the output width, inner rows and kept boundary rows
+      PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
+      BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_out, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
+                                   ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_in, ctx->ws.dis_halo,
+                                   halo_scale(p), dZ, nullptr, nullptr, false, ctx->ws.spmm_partials, G_in, G_halo,
+                                   s));
+    }
+    if (B > 0) {  // the kept boundary features once more, unscaled: G_halo carries the 1/p and degree factors
+      PhaseTimer t(ctx, BNS_PHASE_GATHER, s);
+      BNS_TRY("halo_gather", halo_gather(halo_first, ctx->cur_kept, ctx->cur_n_kept, B, nullptr, 1.f, d_in,
+                                         ctx->ws.Hu, s));
+    }
+    {
+      PhaseTimer t(ctx, BNS_PHASE_GEMM_DW, s);
+      BNS_TRY("gemm_tn_splitk(inner)", gemm_tn_splitk(d_in, d_out, n_in, H_in, G_in, dW, ctx->ws.partials, false,
+                                                      nullptr, s));
+      if (B > 0)
+        BNS_TRY("gemm_tn_splitk(boundary)", gemm_tn_splitk(d_in, d_out, B, ctx->ws.Hu, G_halo, dW, ctx->ws.partials,
+                                                           true, ctx->cur_n_kept, s));
+    }
+    if (dH_in) {
+      PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
+      const float ms1 = mask_src ? mask_scale_of(ctx) : 1.f;
+      BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, G_in, W, dH_in, mask_src, ms1, nullptr, s));
+      if (dhalo && B > 0)
+        BNS_TRY("gemm_nt(halo)", gemm_nt(B, d_in, d_out, G_halo, W, dhalo, nullptr, 1.f, ctx->cur_n_kept, s));
+    }
+    return BNS_OK;
+  }
   // slope of the surviving hidden units of the layer below (dropout); it multiplies the masked
   // gradient only.  Where the transposed aggregate applies the mask, the factor rides on its
   // input (the product with W^T) and is divided out of the boundary rows, which are not masked.
@@ -286,8 +368,10 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
     const size_t half = (size_t)d_in * d_out;
     {
       PhaseTimer t(ctx, BNS_PHASE_GEMM_DW, s);
-      BNS_TRY("gemm_tn_splitk(nbr)", gemm_tn_splitk(d_in, d_out, n_in, A_saved, dZ, dW, ctx->ws.partials, s));
-      BNS_TRY("gemm_tn_splitk(self)", gemm_tn_splitk(d_in, d_out, n_in, H_in, dZ, dW + half, ctx->ws.partials, s));
+      BNS_TRY("gemm_tn_splitk(nbr)", gemm_tn_splitk(d_in, d_out, n_in, A_saved, dZ, dW, ctx->ws.partials, false,
+                                                    nullptr, s));
+      BNS_TRY("gemm_tn_splitk(self)", gemm_tn_splitk(d_in, d_out, n_in, H_in, dZ, dW + half, ctx->ws.partials, false,
+                                                     nullptr, s));
     }
     if (dH_in) {
       {
@@ -306,7 +390,7 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
   }
   {
     PhaseTimer t(ctx, BNS_PHASE_GEMM_DW, s);
-    BNS_TRY("gemm_tn_splitk", gemm_tn_splitk(d_in, d_out, n_in, A_saved, dZ, dW, ctx->ws.partials, s));
+    BNS_TRY("gemm_tn_splitk", gemm_tn_splitk(d_in, d_out, n_in, A_saved, dZ, dW, ctx->ws.partials, false, nullptr, s));
   }
   if (dH_in && d_out < d_in) {
     // (P^T dZ) W^T instead of P^T (dZ W^T): the transposed aggregate runs at the narrower width
@@ -448,7 +532,7 @@ bns_status bns_gcn_layer_fwd(bns_ctx *ctx, int32_t layer, double p, const float 
   if (!H_in || !W || !A_saved || !H_out || (ctx->part.n_halo > 0 && !halo_h))
     return fail(ctx, BNS_EINVAL, "null pointer");
   if (!ctx->cur_row_ptr) return fail(ctx, BNS_EINVAL, "bns_build_sampled_csr has not been called");
-  return layer_fwd_impl(ctx, layer, p, H_in, halo_h, W, A_saved, H_out, relu != 0,
+  return layer_fwd_impl(ctx, layer, p, H_in, halo_h, W, A_saved, H_out, relu != 0, false,
                         static_cast<hipStream_t>(stream));
 }
 
@@ -469,7 +553,7 @@ bns_status bns_gcn_layer_bwd(bns_ctx *ctx, int32_t layer, double p, const float 
     BNS_TRY("relu_mask", relu_mask(n, dH_out, H_out, mask_scale_of(ctx), ctx->ws.G0, s));
     dZ = ctx->ws.G0;
   }
-  return layer_bwd_impl(ctx, layer, p, dZ, A_saved, H_in, W, dW, dH_in, dhalo, nullptr, s);
+  return layer_bwd_impl(ctx, layer, p, dZ, A_saved, H_in, W, dW, dH_in, dhalo, nullptr, false, nullptr, s);
 }
 
 static bns_status train_step_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, const uint32_t *epoch_dev, double p,
@@ -494,7 +578,7 @@ static bns_status train_step_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, c
   const float *H_prev = X;
   for (int l = 1; l <= L; ++l) {
     st = layer_fwd_impl(ctx, l, p, H_prev, ctx->part.n_halo > 0 ? halo_h[l - 1] : nullptr, W[l - 1], w.A[l],
-                        w.H[l], l < L, s);
+                        w.H[l], l < L, layer_plan(ctx, l, X) == BNS_LAYER_UPDATE_FIRST, s);
     if (st != BNS_OK) return st;
     H_prev = w.H[l];
   }
@@ -516,7 +600,8 @@ static bns_status train_step_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, c
     float *dh = (dhalo && l > 1) ? dhalo[l - 1] : nullptr;
     st = layer_bwd_impl(ctx, l, p, w.G0, w.A[l], l > 1 ? w.H[l - 1] : X, W[l - 1], dW[l - 1],
                         l > 1 ? w.G0 : nullptr, dh,
-                        l > 1 ? w.H[l - 1] : nullptr, s);
+                        l > 1 ? w.H[l - 1] : nullptr, layer_plan(ctx, l, X) == BNS_LAYER_UPDATE_FIRST,
+                        ctx->part.n_halo > 0 ? halo_h[l - 1] : nullptr, s);
     if (st != BNS_OK) return st;
   }
   if (lr > 0.f) {
@@ -568,9 +653,9 @@ bns_status bns_graph_replay(bns_ctx *ctx, int32_t n_epochs, void *stream) {
   return BNS_OK;
 }
 
-int32_t bns_layer_is_fused(const bns_ctx *ctx, int32_t layer) {
-  if (!ctx || layer < 1 || layer >= (int32_t)ctx->dims.size()) return 0;
-  return ctx->layer_kind == 0 && spmm_gemm_fwd_supported(ctx->dims[layer - 1]) ? 1 : 0;
+int32_t bns_layer_plan(const bns_ctx *ctx, int32_t layer) {
+  if (!ctx || layer < 1 || layer >= (int32_t)ctx->dims.size()) return -1;
+  return layer_plan(ctx, layer, ctx->cache_X);
 }
 
 bns_status bns_set_dropout(bns_ctx *ctx, double q) {
@@ -602,7 +687,7 @@ bns_status bns_cache_input_aggregate(bns_ctx *ctx, const float *X, void *stream)
   part.skip_self = sage;
   BNS_TRY("spmm_fwd(cache)", spmm_fwd(ctx->ws.plan_f, ctx->part.n_in, ctx->dims[0], ctx->part.row_ptr0,
                                       ctx->part.col0, sage ? nullptr : ctx->ws.dis_in, nullptr, X, nullptr,
-                                      ctx->ws.spmm_partials, ctx->ws.C0, part, false, s));
+                                      ctx->ws.spmm_partials, ctx->ws.C0, part, false, false, s));
   ctx->cache_X = X;
   return BNS_OK;
 }

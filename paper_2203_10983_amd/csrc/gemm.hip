@@ -103,16 +103,18 @@ __device__ __forceinline__ void store_ncontig(const FragN<COLS> &f, float *__res
 // the ReLU output goes through dropout: a lane owns four consecutive rows of one column per
 // accumulator quad, which is exactly one Philox call.
 // m_dev (nullable): the row count lives on the device (*m_dev <= M); tiles past it do nothing.
+// k_dev (nullable): the depth lives on the device (*k_dev <= K); steps past it contribute nothing.
 template <int BN, bool A_KCONTIG, bool B_KCONTIG, int EPI>
 __global__ void __launch_bounds__(kGemmThreads, 4)
 gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const float *__restrict__ B,
             int ldb, float *__restrict__ C, int ldc, int k_chunk, bool vec_a, bool vec_b,
             const float *__restrict__ mask_src, float alpha, const int *__restrict__ m_dev,
-            const Dropout drop) {
+            const int *__restrict__ k_dev, const Dropout drop) {
   constexpr int LDA = BM + 4, LDB = BN + 4;  // row strides of the staged tiles (16-byte aligned rows)
   constexpr int TI = BN == 128 ? 2 : 1;      // 32-row MFMA tiles per wavefront
   const int m_full = M;
   if (m_dev) M = min(M, *m_dev);
+  if (k_dev) K = min(K, *k_dev);  // the depth lives on the device (kept boundary rows)
   __shared__ __attribute__((aligned(16))) float As[2][BK * LDA];
   __shared__ __attribute__((aligned(16))) float Bs[2][BK * LDB];
 
@@ -232,16 +234,16 @@ static inline unsigned n_tiles(int M, int N, int bn) {
   } while (0)
 
 hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   bool relu, bool accumulate, const Dropout &drop, hipStream_t s) {
+                   bool relu, bool accumulate, const Dropout &drop, const int32_t *m_dev, hipStream_t s) {
   const int bn = pick_bn(N);
   const unsigned tiles = n_tiles(M, N, bn);
   if (tiles == 0) return hipSuccess;
   const bool va = (K % 4 == 0) && aligned16(A), vb = (N % 4 == 0) && aligned16(B);
   const dim3 grid(tiles, 1);
-  if (accumulate && relu) BNS_GEMM_LAUNCH(true, false, 4, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, nullptr, drop);
-  else if (accumulate) BNS_GEMM_LAUNCH(true, false, 3, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, nullptr, drop);
-  else if (relu) BNS_GEMM_LAUNCH(true, false, 1, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, nullptr, drop);
-  else BNS_GEMM_LAUNCH(true, false, 0, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, nullptr, drop);
+  if (accumulate && relu) BNS_GEMM_LAUNCH(true, false, 4, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop);
+  else if (accumulate) BNS_GEMM_LAUNCH(true, false, 3, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop);
+  else if (relu) BNS_GEMM_LAUNCH(true, false, 1, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop);
+  else BNS_GEMM_LAUNCH(true, false, 0, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop);
   return hipGetLastError();
 }
 
@@ -252,8 +254,8 @@ hipError_t gemm_nt(int32_t M, int32_t N, int32_t K, const float *A, const float 
   if (tiles == 0) return hipSuccess;
   const bool va = (K % 4 == 0) && aligned16(A), vb = (K % 4 == 0) && aligned16(B);
   const dim3 grid(tiles, 1);
-  if (mask_src) BNS_GEMM_LAUNCH(true, true, 2, grid, M, N, K, A, K, B, K, C, N, K, va, vb, mask_src, alpha, m_dev, Dropout{});
-  else BNS_GEMM_LAUNCH(true, true, 0, grid, M, N, K, A, K, B, K, C, N, K, va, vb, nullptr, alpha, m_dev, Dropout{});
+  if (mask_src) BNS_GEMM_LAUNCH(true, true, 2, grid, M, N, K, A, K, B, K, C, N, K, va, vb, mask_src, alpha, m_dev, nullptr, Dropout{});
+  else BNS_GEMM_LAUNCH(true, true, 0, grid, M, N, K, A, K, B, K, C, N, K, va, vb, nullptr, alpha, m_dev, nullptr, Dropout{});
   return hipGetLastError();
 }
 
@@ -284,18 +286,20 @@ int32_t splitk_splits(int32_t M, int32_t N, int32_t K) {
 
 // out[g][i] = sum over the splits z of group g (in ascending z) of in[z][i]
 __global__ void __launch_bounds__(256)
-splitk_reduce_kernel(const float *__restrict__ in, float *__restrict__ out, int64_t mn, int splits) {
+splitk_reduce_kernel(const float *__restrict__ in, float *__restrict__ out, int64_t mn, int splits,
+                     bool add_to_out) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= mn) return;
   const int z0 = blockIdx.y * kReduceGroup;
   const int z1 = min(splits, z0 + kReduceGroup);
   float sum = 0.f;
   for (int z = z0; z < z1; ++z) sum += in[(size_t)z * mn + i];
+  if (add_to_out) sum += out[(size_t)blockIdx.y * mn + i];
   out[(size_t)blockIdx.y * mn + i] = sum;
 }
 
 hipError_t gemm_tn_splitk(int32_t M, int32_t N, int32_t K, const float *A, const float *B,
-                          float *C, float *partials, hipStream_t s) {
+                          float *C, float *partials, bool accumulate, const int32_t *k_dev, hipStream_t s) {
   const int bn = pick_bn(N);
   const unsigned tiles = n_tiles(M, N, bn);
   if (tiles == 0) return hipSuccess;
@@ -305,7 +309,10 @@ hipError_t gemm_tn_splitk(int32_t M, int32_t N, int32_t K, const float *A, const
   const int64_t mn = (int64_t)M * N;
   float *dst = splits == 1 ? C : partials;
   const dim3 grid(tiles, splits);
-  BNS_GEMM_LAUNCH(false, false, 0, grid, M, N, K, A, M, B, N, dst, N, chunk, va, vb, nullptr, 1.f, nullptr, Dropout{});
+  if (splits == 1 && accumulate)
+    BNS_GEMM_LAUNCH(false, false, 3, grid, M, N, K, A, M, B, N, dst, N, chunk, va, vb, nullptr, 1.f, nullptr, k_dev, Dropout{});
+  else
+    BNS_GEMM_LAUNCH(false, false, 0, grid, M, N, K, A, M, B, N, dst, N, chunk, va, vb, nullptr, 1.f, nullptr, k_dev, Dropout{});
   // grouped, fixed-order reduction: partials -> level 2 -> ... -> C
   float *cur = partials;
   float *nxt = partials + (size_t)splits * mn;
@@ -313,7 +320,8 @@ hipError_t gemm_tn_splitk(int32_t M, int32_t N, int32_t K, const float *A, const
   while (n > 1) {
     const int groups = (n + kReduceGroup - 1) / kReduceGroup;
     float *out = groups == 1 ? C : nxt;
-    splitk_reduce_kernel<<<dim3((unsigned)((mn + 255) / 256), groups), 256, 0, s>>>(cur, out, mn, n);
+    splitk_reduce_kernel<<<dim3((unsigned)((mn + 255) / 256), groups), 256, 0, s>>>(cur, out, mn, n,
+                                                                                  accumulate && groups == 1);
     float *t = cur; cur = nxt; nxt = t;   // ping-pong (level >= 3 reuses the first buffer)
     n = groups;
   }

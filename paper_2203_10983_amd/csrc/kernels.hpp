@@ -97,7 +97,7 @@ struct SpmmRowPart {
 hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
                     const int32_t *col_idx, const float *w_col, const float *row_scale,
                     const float *H_in, const float *Hu, float *partials, float *A,
-                    const SpmmRowPart &part, bool long_rows_only, hipStream_t s);
+                    const SpmmRowPart &part, bool long_rows_only, bool relu, hipStream_t s);
 // Aggregate and update of one GCN layer in one kernel (Eq. 1 then Eq. 2): a workgroup aggregates 64
 // rows into LDS (and stores them to A, which the backward pass needs), then multiplies the tile by
 // W on the matrix cores while other workgroups of the same compute unit keep gathering.  Rows cut
@@ -132,8 +132,9 @@ struct Dropout {
 };
 // C[M,N] = A[M,K] B[K,N] (+ the previous C if accumulate), then optional ReLU (followed by dropout
 // when drop.scale != 0).
+// m_dev (nullable): device-side row count, *m_dev <= M; rows past it are not touched.
 hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   bool relu, bool accumulate, const Dropout &drop, hipStream_t s);
+                   bool relu, bool accumulate, const Dropout &drop, const int32_t *m_dev, hipStream_t s);
 // inv[i] = deg[i] > 1 ? 1 / (deg[i] - 1) : 0   (deg counts the self-loop)
 hipError_t degree_inverse(const int32_t *deg, int32_t n, float *inv, hipStream_t s);
 // C[M,N] = alpha * A[M,K] B[N,K]^T.  mask_src (nullable, [M,N]): C is zeroed where mask_src <= 0.
@@ -143,8 +144,10 @@ hipError_t gemm_nt(int32_t M, int32_t N, int32_t K, const float *A, const float 
 // C[M,N] = A[K,M]^T B[K,N] with K split over the grid; partials: scratch f32[splits*M*N],
 // summed in a fixed order.  splitk_splits() gives the split count used for (M,N,K).
 int32_t splitk_splits(int32_t M, int32_t N, int32_t K);
+// accumulate: the product is added to C.  k_dev (nullable): device-side depth, *k_dev <= K (the
+// partial buffer is still sized by splitk_splits(M, N, K)).
 hipError_t gemm_tn_splitk(int32_t M, int32_t N, int32_t K, const float *A, const float *B,
-                          float *C, float *partials, hipStream_t s);
+                          float *C, float *partials, bool accumulate, const int32_t *k_dev, hipStream_t s);
 
 // ---- loss.hip (Algorithm 1, loss step) ---------------------------------------------------------
 constexpr int kLossBlocks = 8192;  // partials: scratch f32[kLossBlocks]
@@ -152,6 +155,8 @@ hipError_t loss_softmax_ce(int32_t n, int32_t C, const float *logits, const int3
                            float *dZ, float *partials, float *loss, hipStream_t s);
 hipError_t loss_sigmoid_bce(int32_t n, int32_t C, const float *logits, const uint8_t *labels,
                             float *dZ, float *partials, float *loss, hipStream_t s);
+// Dropout applied in place to H[n_rows, d] (for layers whose ReLU sits in the aggregate's store).
+hipError_t dropout_inplace(int32_t n_rows, int32_t d, float *H, const Dropout &drop, hipStream_t s);
 // out = scale * dH where H > 0 else 0
 hipError_t relu_mask(int64_t n, const float *dH, const float *H, float scale, float *out, hipStream_t s);
 // Adam step t (1-based) on n weights; m, v are the caller's moment buffers.

@@ -191,9 +191,10 @@ static hipError_t launch_spmm(const SpmmArgs &a, int64_t max_units, hipStream_t 
 hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
                     const int32_t *col_idx, const float *w_col, const float *row_scale,
                     const float *H_in, const float *Hu, float *partials, float *A,
-                    const SpmmRowPart &part, bool long_rows_only, hipStream_t s) {
+                    const SpmmRowPart &part, bool long_rows_only, bool relu, hipStream_t s) {
   SpmmArgs a = spmm_fwd_args(plan, n_in, d, row_ptr, col_idx, w_col, row_scale, H_in, Hu, partials, A, part);
   a.multi_only = long_rows_only;
+  a.relu = relu;
   return launch_spmm(a, plan.n_seg, s);
 }
 
@@ -289,22 +290,39 @@ __global__ void __launch_bounds__(256)
 halo_gather_kernel(const float *__restrict__ halo_h, const int32_t *__restrict__ kept_ids,
                    const int32_t *__restrict__ n_kept, const float *__restrict__ dis_halo,
                    float s_halo, int32_t d, float *__restrict__ Hu) {
+  // one VEC-piece of one kept row per thread and step, consecutive threads on consecutive pieces
+  // (a wavefront covers 64 / (d / VEC) rows); four independent pieces in flight per thread
   using V = typename Vec<VEC>::T;
-  const int lane = lane_id();
-  const int n = *n_kept;
-  const int nvec = d / VEC;
-  const int waves = gridDim.x * 4;
-  for (int r = blockIdx.x * 4 + (threadIdx.x >> 6); r < n; r += waves) {
-    const int b = kept_ids[r];
-    const float sc = dis_halo ? s_halo * dis_halo[b] : s_halo;
-    const V *src = reinterpret_cast<const V *>(halo_h + (size_t)b * d);
-    V *dst = reinterpret_cast<V *>(Hu + (size_t)r * d);
-    for (int iv = lane; iv < nvec; iv += kWave) {
-      V x = src[iv];
-      float *px = reinterpret_cast<float *>(&x);
+  constexpr int UNR = 4;
+  const unsigned nvec = (unsigned)(d / VEC);
+  const long long total = (long long)*n_kept * nvec;
+  const long long stride = (long long)gridDim.x * 256;
+  const bool small = total + stride * UNR < 0x7fffffffLL;  // 32-bit division suffices
+  for (long long t0 = (long long)blockIdx.x * 256 + threadIdx.x; t0 < total; t0 += stride * UNR) {
+    int b[UNR];
+    unsigned iv[UNR];
+    long long t[UNR];
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) px[i] *= sc;
-      dst[iv] = x;
+    for (int u = 0; u < UNR; ++u) {
+      t[u] = t0 + u * stride;
+      const unsigned r = small ? (unsigned)t[u] / nvec : (unsigned)(t[u] / nvec);
+      iv[u] = (unsigned)(t[u] - (long long)r * nvec);
+      b[u] = t[u] < total ? kept_ids[r] : -1;
+    }
+    float sc[UNR];
+    V x[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      sc[u] = (b[u] >= 0 && dis_halo) ? s_halo * dis_halo[b[u]] : s_halo;
+      if (b[u] >= 0) x[u] = reinterpret_cast<const V *>(halo_h + (size_t)b[u] * d)[iv[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      if (b[u] < 0) continue;
+      float *px = reinterpret_cast<float *>(&x[u]);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) px[i] *= sc[u];
+      reinterpret_cast<V *>(Hu)[t[u]] = x[u];   // row r, piece iv: Hu is dense, so the piece index is t
     }
   }
 }
@@ -313,8 +331,9 @@ hipError_t halo_gather(const float *halo_h, const int32_t *kept_ids, const int32
                        int32_t n_halo, const float *dis_halo, float s_halo, int32_t d, float *Hu,
                        hipStream_t s) {
   if (n_halo <= 0) return hipSuccess;
-  int64_t blocks = ((int64_t)n_halo + 3) / 4;
-  if (blocks > 8192) blocks = 8192;
+  const int vec = d % 4 == 0 ? 4 : d % 2 == 0 ? 2 : 1;
+  int64_t blocks = ((int64_t)n_halo * (d / vec) + 1023) / 1024;  // sized for every boundary node kept
+  if (blocks > 4096) blocks = 4096;
   if (d % 4 == 0)
     halo_gather_kernel<4><<<(unsigned)blocks, 256, 0, s>>>(halo_h, kept_ids, n_kept, dis_halo, s_halo, d, Hu);
   else if (d % 2 == 0)

@@ -46,6 +46,7 @@ struct SpmmArgs {
   // times as many distinct rows.
   int32_t n_slices, d_slice;
   bool multi_only;             // work units = segments of the multi-segment rows only
+  bool relu;                   // rows < n_split: max(., 0) after the scale (update-first layers)
 };
 
 // Argument block of the forward aggregate (the transposed pass fills its own).
@@ -61,7 +62,7 @@ inline SpmmArgs spmm_fwd_args(const SegPlan &plan, int32_t n_in, int32_t d, cons
   a.kept_ids = nullptr; a.dis_halo = nullptr; a.s_halo = 0.f;
   a.row_skip = part.row_skip; a.row_take = part.row_take; a.init = part.init;
   a.skip_self = part.skip_self;
-  a.n_slices = 1; a.d_slice = d; a.multi_only = false;
+  a.n_slices = 1; a.d_slice = d; a.multi_only = false; a.relu = false;
   return a;
 }
 
@@ -103,6 +104,10 @@ __device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, i
       }
 #pragma unroll
       for (int i = 0; i < VEC; ++i) po[i] *= scale;
+      if (a.relu) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) po[i] = fmaxf(po[i], 0.f);
+      }
       if (mask) {
         const V m = reinterpret_cast<const V *>(mask)[iv];
         const float *pm = reinterpret_cast<const float *>(&m);
