@@ -47,6 +47,12 @@ __device__ __forceinline__ void load_kcontig(FragK<ROWS> &f, const float *__rest
                                              int row0, int n_rows, int k0, int k_end, bool vec_ok) {
   const int t = threadIdx.x;
   const int kq = (t & 3) * 4;
+  if (vec_ok && row0 + ROWS <= n_rows && k0 + BK <= k_end) {  // whole tile in range (uniform over the block)
+#pragma unroll
+    for (int p = 0; p < ROWS / 64; ++p)
+      f.v[p] = *reinterpret_cast<const float4 *>(base + (size_t)(row0 + (t >> 2) + p * 64) * ld + k0 + kq);
+    return;
+  }
 #pragma unroll
   for (int p = 0; p < ROWS / 64; ++p) {
     const int r = row0 + (t >> 2) + p * 64;
@@ -77,6 +83,12 @@ __device__ __forceinline__ void load_ncontig(FragN<COLS> &f, const float *__rest
   constexpr int KPP = kGemmThreads / TPR;    // k-rows per pass
   const int t = threadIdx.x;
   const int cq = (t % TPR) * 4;
+  if (vec_ok && col0 + COLS <= n_cols && k0 + BK <= k_end) {  // whole tile in range (uniform over the block)
+#pragma unroll
+    for (int p = 0; p < BK / KPP; ++p)
+      f.v[p] = *reinterpret_cast<const float4 *>(base + (size_t)(k0 + t / TPR + p * KPP) * ld + col0 + cq);
+    return;
+  }
 #pragma unroll
   for (int p = 0; p < BK / KPP; ++p) {
     const int k = k0 + t / TPR + p * KPP;
