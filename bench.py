@@ -143,6 +143,11 @@ def main():
                   "gemm_da": sum(2 * kw * n_in * dims[l - 1] * dims[l] for l in range(2, L + 1))}
     per_step_ms = {k: v[0] / args.steps for k, v in phases.items()}
     launches = {k: v[1] // args.steps for k, v in phases.items()}
+    # the forward aggregate class = the one-kernel / plain aggregate launches plus, before one-kernel layers,
+    # the pass over the rows longer than one segment (timed apart so that launch times match a kernel trace)
+    long_ms = per_step_ms.pop("spmm_long")
+    fwd_kernel_ms = per_step_ms["spmm_fwd"]
+    per_step_ms["spmm_fwd"] += long_ms
     cand = {k: per_step_ms[k] for k in ("spmm_fwd", "spmm_bwd", "gemm_fwd", "gemm_dw", "gemm_da")}
     dom = max(cand, key=cand.get)
     if dom.startswith("spmm"):
@@ -152,6 +157,13 @@ def main():
                 "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                 "launches_per_step": launches[dom], "avg_launch_ms": per_step_ms[dom] / max(launches[dom], 1),
                 "algorithmic_bytes_per_step": alg}
+        if dom == "spmm_fwd" and fused:
+            # per launch: the dominant kernel itself, and the long-row pass that precedes it
+            roof["avg_launch_ms"] = fwd_kernel_ms / max(launches[dom], 1)
+            roof["kernel_name"] = "spmm_gemm_kernel (aggregate + update)"
+            roof["long_row_pass_ms_per_launch"] = long_ms / max(launches[dom], 1)
+            roof["note"] = ("achieved = algorithmic bytes of the layer / (long-row pass + one-kernel launch); "
+                            "avg_launch_ms is the one-kernel launch alone, as a kernel trace shows it")
     else:
         fl = gemm_flops[dom]
         achieved = fl / (per_step_ms[dom] * 1e-3) / 1e12
@@ -172,6 +184,7 @@ def main():
         "spmm_fwd_GBps": fwd_bytes / (per_step_ms["spmm_fwd"] * 1e-3) / 1e9 if per_step_ms["spmm_fwd"] else None,
         "spmm_bwd_GBps": bwd_bytes / (per_step_ms["spmm_bwd"] * 1e-3) / 1e9 if per_step_ms["spmm_bwd"] else None,
     }
+    classes["spmm_fwd_long_row_pass_ms"] = long_ms      # part of spmm_fwd above
     for k, fl in gemm_flops.items():
         classes[k + "_TFLOPs"] = fl / (per_step_ms[k] * 1e-3) / 1e12 if per_step_ms[k] else None
 

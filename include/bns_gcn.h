@@ -251,7 +251,9 @@ typedef enum {
   BNS_PHASE_GEMM_DA = 7,  /* dZ W^T                                        */
   BNS_PHASE_SPMM_BWD = 8, /* transposed aggregate                          */
   BNS_PHASE_SGD = 9,
-  BNS_PHASE_COUNT = 10
+  BNS_PHASE_SPMM_LONG = 10, /* forward aggregate of the rows longer than one segment, where it
+                               runs as a pass of its own before a one-kernel layer */
+  BNS_PHASE_COUNT = 11
 } bns_phase;
 bns_status bns_profile_enable(bns_ctx *ctx, uint32_t phase_mask, int32_t max_records);
 bns_status bns_profile_read(bns_ctx *ctx, double *ms_per_phase /* host [BNS_PHASE_COUNT] */,

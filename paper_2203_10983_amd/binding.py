@@ -21,7 +21,7 @@ EXPORTED = ["bns_workspace_bytes", "bns_create", "bns_destroy", "bns_last_error"
             "bns_profile_enable", "bns_profile_read"]
 
 PHASES = ["sample", "build", "gather", "spmm_fwd", "gemm_fwd", "loss", "gemm_dw", "gemm_da",
-          "spmm_bwd", "sgd"]
+          "spmm_bwd", "sgd", "spmm_long"]
 
 VIEW_KEPT_IDS, VIEW_REMAP, VIEW_N_KEPT, VIEW_ROW_PTR, VIEW_COL_IDX = 0, 1, 2, 3, 4
 VIEW_T_ROW_PTR, VIEW_T_COL_IDX, VIEW_NNZ, VIEW_A, VIEW_H = 5, 6, 7, 8, 9

@@ -291,10 +291,13 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
   const float *row_scale = sage ? ctx->ws.inv_deg : ctx->ws.dis_in;
   if (!sage && spmm_gemm_fwd_supported(d_in)) {
     // aggregate and update in one kernel; the rows cut into several segments are finished first
+    {
+      PhaseTimer t(ctx, BNS_PHASE_SPMM_LONG, s);
+      BNS_TRY("spmm_fwd(long rows)", spmm_fwd(ctx->ws.plan_f, n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx, w_col,
+                                              row_scale, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part,
+                                              true, false, s));
+    }
     PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
-    BNS_TRY("spmm_fwd(long rows)", spmm_fwd(ctx->ws.plan_f, n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx, w_col,
-                                            row_scale, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part,
-                                            true, false, s));
     BNS_TRY("spmm_gemm_fwd", spmm_gemm_fwd(ctx->ws.plan_f, n_in, d_in, d_out, ctx->cur_row_ptr, ctx->cur_col_idx,
                                            w_col, row_scale, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved,
                                            part, W, H_out, relu, dropout_of(ctx, layer, relu), s));
