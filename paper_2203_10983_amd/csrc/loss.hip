@@ -47,39 +47,71 @@ softmax_ce_kernel(int n, int C, const float *__restrict__ logits, const int32_t 
   const int lane = lane_id();
   const int waves = gridDim.x * (kT / kWave);
   float loss_acc = 0.f;  // meaningful on lane 0
-  for (int v = blockIdx.x * (kT / kWave) + threadIdx.x / kWave; v < n; v += waves) {
-    const float *z = logits + (size_t)v * C;
-    float *g = dZ + (size_t)v * C;
-    const int y = labels[v];
-    if (y < 0) {  // node outside the training set: no loss, zero gradient
-      for (int c = lane; c < C; c += kWave) g[c] = 0.f;
-      continue;
+  const int v0 = blockIdx.x * (kT / kWave) + threadIdx.x / kWave;
+  if (C <= 4 * kWave) {
+    constexpr int R = 2;
+    // two rows per step, their loads and reductions interleaved; the loss is still added row by
+    // row in ascending order, so the sum does not depend on the pairing
+    for (int v = v0; v < n; v += R * waves) {
+      int row[R], y[R];
+      float x[R][4], m[R], se[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) row[r] = v + r * waves;
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const bool ok = row[r] < n;
+        y[r] = ok ? labels[row[r]] : -1;
+        m[r] = -INFINITY;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int c = lane + k * kWave;
+          x[r][k] = (ok && c < C) ? logits[(size_t)row[r] * C + c] : -INFINITY;
+          m[r] = fmaxf(m[r], x[r][k]);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < R; ++r) m[r] = wave_max(m[r]);
+      float zy[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        se[r] = 0.f;
+        zy[r] = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int c = lane + k * kWave;
+          if (c == y[r]) zy[r] = x[r][k];
+          x[r][k] = c < C ? expf(x[r][k] - m[r]) : 0.f;
+          se[r] += x[r][k];
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        se[r] = wave_sum(se[r]);
+        zy[r] = wave_sum(zy[r]);  // exactly one lane holds z[y]; the others add zeros
+      }
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        if (row[r] >= n) continue;
+        float *g = dZ + (size_t)row[r] * C;
+        const float inv = 1.f / se[r];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int c = lane + k * kWave;
+          // a node outside the training set (negative label): no loss, zero gradient
+          if (c < C) g[c] = y[r] < 0 ? 0.f : x[r][k] * inv - (c == y[r] ? 1.f : 0.f);
+        }
+        if (lane == 0 && y[r] >= 0) loss_acc += (m[r] + logf(se[r])) - zy[r];
+      }
     }
-    if (C <= 4 * kWave) {
-      float x[4];
-      float m = -INFINITY;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int c = lane + k * kWave;
-        x[k] = c < C ? z[c] : -INFINITY;
-        m = fmaxf(m, x[k]);
+  } else {
+    for (int v = v0; v < n; v += waves) {
+      const float *z = logits + (size_t)v * C;
+      float *g = dZ + (size_t)v * C;
+      const int y = labels[v];
+      if (y < 0) {  // node outside the training set: no loss, zero gradient
+        for (int c = lane; c < C; c += kWave) g[c] = 0.f;
+        continue;
       }
-      m = wave_max(m);
-      float se = 0.f;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        x[k] = lane + k * kWave < C ? expf(x[k] - m) : 0.f;
-        se += x[k];
-      }
-      se = wave_sum(se);
-      const float inv = 1.f / se;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int c = lane + k * kWave;
-        if (c < C) g[c] = x[k] * inv - (c == y ? 1.f : 0.f);
-      }
-      if (lane == 0) loss_acc += (m + logf(se)) - z[y];
-    } else {
       float m = -INFINITY;
       for (int c = lane; c < C; c += kWave) m = fmaxf(m, z[c]);
       m = wave_max(m);
