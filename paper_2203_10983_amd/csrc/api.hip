@@ -119,6 +119,8 @@ size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, La
     d_in_max = std::max<size_t>(d_in_max, m->dims[l]);
     const size_t mn = (size_t)m->dims[l] * m->dims[l + 1];
     part_max = std::max(part_max, mn * (size_t)splitk_splits(m->dims[l], m->dims[l + 1], p->n_in));
+    if (m->layer_kind == 1)  // [A | H]^T dZ as one product of twice the height
+      part_max = std::max(part_max, 2 * mn * (size_t)splitk_splits(2 * m->dims[l], m->dims[l + 1], p->n_in));
     if (update_first_shape(m->layer_kind, m->dims[l], m->dims[l + 1])) {
       d_first_max = std::max<size_t>(d_first_max, m->dims[l + 1]);
       if (p->n_halo > 0)
@@ -313,6 +315,9 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
     if (!sage) {
       BNS_TRY("gemm_nn", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, relu, false, dropout_of(ctx, layer, relu),
                                  nullptr, s));
+    } else if (d_in % 16 == 0) {  // [z | h] [W_n ; W_s] in one product
+      BNS_TRY("gemm_nn_concat", gemm_nn_concat(n_in, d_out, d_in, A_saved, H_in, W, H_out, relu,
+                                               dropout_of(ctx, layer, relu), s));
     } else {  // [z | h] [W_n ; W_s] = z W_n + h W_s
       BNS_TRY("gemm_nn(nbr)", gemm_nn(n_in, d_out, d_in, A_saved, W, H_out, false, false, Dropout{}, nullptr, s));
       BNS_TRY("gemm_nn(self)", gemm_nn(n_in, d_out, d_in, H_in, W + (size_t)d_in * d_out, H_out, relu, true,
@@ -371,16 +376,25 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
     const size_t half = (size_t)d_in * d_out;
     {
       PhaseTimer t(ctx, BNS_PHASE_GEMM_DW, s);
-      BNS_TRY("gemm_tn_splitk(nbr)", gemm_tn_splitk(d_in, d_out, n_in, A_saved, dZ, dW, ctx->ws.partials, false,
-                                                    nullptr, s));
-      BNS_TRY("gemm_tn_splitk(self)", gemm_tn_splitk(d_in, d_out, n_in, H_in, dZ, dW + half, ctx->ws.partials, false,
-                                                     nullptr, s));
+      if (gemm_tn_concat_supported(d_in)) {  // [A | H]^T dZ in one product: dZ is read once
+        BNS_TRY("gemm_tn_splitk_concat", gemm_tn_splitk_concat(d_in, d_out, n_in, A_saved, H_in, dZ, dW,
+                                                               ctx->ws.partials, false, nullptr, s));
+      } else {
+        BNS_TRY("gemm_tn_splitk(nbr)", gemm_tn_splitk(d_in, d_out, n_in, A_saved, dZ, dW, ctx->ws.partials, false,
+                                                      nullptr, s));
+        BNS_TRY("gemm_tn_splitk(self)", gemm_tn_splitk(d_in, d_out, n_in, H_in, dZ, dW + half, ctx->ws.partials, false,
+                                                       nullptr, s));
+      }
     }
     if (dH_in) {
       {
         PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
-        BNS_TRY("gemm_nt(nbr)", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, nullptr, ms, nullptr, s));
-        BNS_TRY("gemm_nt(self)", gemm_nt(n_in, d_in, d_out, dZ, W + half, ctx->ws.G2, nullptr, ms, nullptr, s));
+        if (gemm_nt_pair_supported(d_in)) {  // dZ [W_n ; W_s]^T in one product, split into the two halves
+          BNS_TRY("gemm_nt_pair", gemm_nt_pair(n_in, d_in, d_out, dZ, W, ctx->ws.G1, ctx->ws.G2, ms, s));
+        } else {
+          BNS_TRY("gemm_nt(nbr)", gemm_nt(n_in, d_in, d_out, dZ, W, ctx->ws.G1, nullptr, ms, nullptr, s));
+          BNS_TRY("gemm_nt(self)", gemm_nt(n_in, d_in, d_out, dZ, W + half, ctx->ws.G2, nullptr, ms, nullptr, s));
+        }
       }
       // dH_in = (gradient through the node's own feature) + mean^T (gradient of the neighbour mean)
       PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);

@@ -116,12 +116,17 @@ __device__ __forceinline__ void store_ncontig(const FragN<COLS> &f, float *__res
 // accumulator quad, which is exactly one Philox call.
 // m_dev (nullable): the row count lives on the device (*m_dev <= M); tiles past it do nothing.
 // k_dev (nullable): the depth lives on the device (*k_dev <= K); steps past it contribute nothing.
+// A2 (nullable, k-contiguous A only): the operand is the concatenation [A | A2] along the depth,
+// both with row stride lda = a_split (a multiple of 16); for the m-contiguous A of the transposed
+// product it is the concatenation along M (a_split a multiple of 128).  C2 (nullable): the result is the pair
+// [C | C2] split at column c_split (a multiple of the column tile), both with row stride ldc.
 template <int BN, bool A_KCONTIG, bool B_KCONTIG, int EPI>
 __global__ void __launch_bounds__(kGemmThreads, 4)
 gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const float *__restrict__ B,
             int ldb, float *__restrict__ C, int ldc, int k_chunk, bool vec_a, bool vec_b,
             const float *__restrict__ mask_src, float alpha, const int *__restrict__ m_dev,
-            const int *__restrict__ k_dev, const Dropout drop) {
+            const int *__restrict__ k_dev, const Dropout drop, const float *__restrict__ A2, int a_split,
+            float *__restrict__ C2, int c_split) {
   constexpr int LDA = BM + 4, LDB = BN + 4;  // row strides of the staged tiles (16-byte aligned rows)
   constexpr int TI = BN == 128 ? 2 : 1;      // 32-row MFMA tiles per wavefront
   const int m_full = M;
@@ -156,8 +161,20 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
   FA fa;
   FB fb;
   auto load_tiles = [&](int k0) {
-    if constexpr (A_KCONTIG) load_kcontig<BM>(fa, A, lda, bm0, M, k0, k_end, vec_a);
-    else load_ncontig<BM>(fa, A, lda, bm0, M, k0, k_end, vec_a);
+    if constexpr (A_KCONTIG) {
+      const float *Ab = A;
+      int k0a = k0, kea = k_end;
+      if (A2) {  // a depth tile never straddles the seam: a_split is a multiple of BK
+        if (k0 >= a_split) { Ab = A2; k0a = k0 - a_split; kea = k_end - a_split; }
+        else kea = min(k_end, a_split);
+      }
+      load_kcontig<BM>(fa, Ab, lda, bm0, M, k0a, kea, vec_a);
+    } else if (A2) {  // [A | A2] along the columns of the m-contiguous operand: a row tile lies in one of them
+      if (bm0 >= a_split) load_ncontig<BM>(fa, A2, lda, bm0 - a_split, a_split, k0, k_end, vec_a);
+      else load_ncontig<BM>(fa, A, lda, bm0, a_split, k0, k_end, vec_a);
+    } else {
+      load_ncontig<BM>(fa, A, lda, bm0, M, k0, k_end, vec_a);
+    }
     if constexpr (B_KCONTIG) load_kcontig<BN>(fb, B, ldb, bn0, N, k0, k_end, vec_b);
     else load_ncontig<BN>(fb, B, ldb, bn0, N, k0, k_end, vec_b);
   };
@@ -198,8 +215,10 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
   for (int i = 0; i < TI; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int col = bn0 + wn + j * 32 + l32;
+      int col = bn0 + wn + j * 32 + l32;
       if (col >= N) continue;
+      float *Cd = C;
+      if (C2 && col >= c_split) { Cd = C2; col -= c_split; }  // column tiles never straddle c_split
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         const int row4 = bm0 + wm + i * 32 + q4 * 8 + lhi * 4;  // a multiple of 4
@@ -214,14 +233,14 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
           const int row = row4 + rr;
           if (row < M) {
             float x = acc[i][j][q4 * 4 + rr];
-            if (EPI == 3 || EPI == 4) x += C[(size_t)row * ldc + col];
+            if (EPI == 3 || EPI == 4) x += Cd[(size_t)row * ldc + col];
             if (EPI == 1 || EPI == 4) {
               x = fmaxf(x, 0.f);
               if (drop.scale != 0.f) x = (uint64_t)u[rr] < drop.threshold ? x * drop.scale : 0.f;
             }
             if (EPI == 2) x = mask_src[(size_t)row * ldc + col] > 0.f ? x * alpha : 0.f;
             if (EPI == 0) x *= alpha;
-            C[(size_t)row * ldc + col] = x;
+            Cd[(size_t)row * ldc + col] = x;
           }
         }
       }
@@ -252,10 +271,39 @@ hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float 
   if (tiles == 0) return hipSuccess;
   const bool va = (K % 4 == 0) && aligned16(A), vb = (N % 4 == 0) && aligned16(B);
   const dim3 grid(tiles, 1);
-  if (accumulate && relu) BNS_GEMM_LAUNCH(true, false, 4, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop);
-  else if (accumulate) BNS_GEMM_LAUNCH(true, false, 3, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop);
-  else if (relu) BNS_GEMM_LAUNCH(true, false, 1, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop);
-  else BNS_GEMM_LAUNCH(true, false, 0, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop);
+  if (accumulate && relu) BNS_GEMM_LAUNCH(true, false, 4, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop, nullptr, 0, nullptr, 0);
+  else if (accumulate) BNS_GEMM_LAUNCH(true, false, 3, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop, nullptr, 0, nullptr, 0);
+  else if (relu) BNS_GEMM_LAUNCH(true, false, 1, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop, nullptr, 0, nullptr, 0);
+  else BNS_GEMM_LAUNCH(true, false, 0, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop, nullptr, 0, nullptr, 0);
+  return hipGetLastError();
+}
+
+hipError_t gemm_nn_concat(int32_t M, int32_t N, int32_t K_half, const float *A1, const float *A2,
+                          const float *B, float *C, bool relu, const Dropout &drop, hipStream_t s) {
+  if (K_half % BK != 0) return hipErrorInvalidValue;
+  const int bn = pick_bn(N);
+  const unsigned tiles = n_tiles(M, N, bn);
+  if (tiles == 0) return hipSuccess;
+  const int K = 2 * K_half;
+  const bool va = (K_half % 4 == 0) && aligned16(A1) && aligned16(A2), vb = (N % 4 == 0) && aligned16(B);
+  const dim3 grid(tiles, 1);
+  if (relu) BNS_GEMM_LAUNCH(true, false, 1, grid, M, N, K, A1, K_half, B, N, C, N, K, va, vb, nullptr, 1.f, nullptr, nullptr, drop, A2, K_half, nullptr, 0);
+  else BNS_GEMM_LAUNCH(true, false, 0, grid, M, N, K, A1, K_half, B, N, C, N, K, va, vb, nullptr, 1.f, nullptr, nullptr, drop, A2, K_half, nullptr, 0);
+  return hipGetLastError();
+}
+
+bool gemm_nt_pair_supported(int32_t N_half) { return N_half % 64 == 0; }
+
+hipError_t gemm_nt_pair(int32_t M, int32_t N_half, int32_t K, const float *A, const float *B, float *C1,
+                        float *C2, float alpha, hipStream_t s) {
+  if (!gemm_nt_pair_supported(N_half)) return hipErrorInvalidValue;
+  const int N = 2 * N_half;
+  const int bn = N_half % 128 == 0 ? 128 : 64;  // a column tile must not straddle the two results
+  const unsigned tiles = n_tiles(M, N, bn);
+  if (tiles == 0) return hipSuccess;
+  const bool va = (K % 4 == 0) && aligned16(A), vb = (K % 4 == 0) && aligned16(B);
+  const dim3 grid(tiles, 1);
+  BNS_GEMM_LAUNCH(true, true, 0, grid, M, N, K, A, K, B, K, C1, N_half, K, va, vb, nullptr, alpha, nullptr, nullptr, Dropout{}, nullptr, 0, C2, N_half);
   return hipGetLastError();
 }
 
@@ -266,8 +314,8 @@ hipError_t gemm_nt(int32_t M, int32_t N, int32_t K, const float *A, const float 
   if (tiles == 0) return hipSuccess;
   const bool va = (K % 4 == 0) && aligned16(A), vb = (K % 4 == 0) && aligned16(B);
   const dim3 grid(tiles, 1);
-  if (mask_src) BNS_GEMM_LAUNCH(true, true, 2, grid, M, N, K, A, K, B, K, C, N, K, va, vb, mask_src, alpha, m_dev, nullptr, Dropout{});
-  else BNS_GEMM_LAUNCH(true, true, 0, grid, M, N, K, A, K, B, K, C, N, K, va, vb, nullptr, alpha, m_dev, nullptr, Dropout{});
+  if (mask_src) BNS_GEMM_LAUNCH(true, true, 2, grid, M, N, K, A, K, B, K, C, N, K, va, vb, mask_src, alpha, m_dev, nullptr, Dropout{}, nullptr, 0, nullptr, 0);
+  else BNS_GEMM_LAUNCH(true, true, 0, grid, M, N, K, A, K, B, K, C, N, K, va, vb, nullptr, alpha, m_dev, nullptr, Dropout{}, nullptr, 0, nullptr, 0);
   return hipGetLastError();
 }
 
@@ -312,19 +360,33 @@ splitk_reduce_kernel(const float *__restrict__ in, float *__restrict__ out, int6
 
 hipError_t gemm_tn_splitk(int32_t M, int32_t N, int32_t K, const float *A, const float *B,
                           float *C, float *partials, bool accumulate, const int32_t *k_dev, hipStream_t s) {
+  return gemm_tn_splitk_concat(M, N, K, A, nullptr, B, C, partials, accumulate, k_dev, s);
+}
+
+bool gemm_tn_concat_supported(int32_t M_half) { return M_half % BM == 0; }
+
+// A2 != nullptr: C[2 M, N] = [A | A2]^T B with A, A2 [K, M] (M here is the width of one of them).
+hipError_t gemm_tn_splitk_concat(int32_t M, int32_t N, int32_t K, const float *A, const float *A2, const float *B,
+                                 float *C, float *partials, bool accumulate, const int32_t *k_dev,
+                                 hipStream_t s) {
+  const int M_half = M;
+  if (A2) {
+    if (!gemm_tn_concat_supported(M_half)) return hipErrorInvalidValue;
+    M = 2 * M_half;
+  }
   const int bn = pick_bn(N);
   const unsigned tiles = n_tiles(M, N, bn);
   if (tiles == 0) return hipSuccess;
   int splits;
   const int chunk = splitk_chunk(M, N, K, &splits);
-  const bool va = (M % 4 == 0) && aligned16(A), vb = (N % 4 == 0) && aligned16(B);
+  const bool va = (M_half % 4 == 0) && aligned16(A) && aligned16(A2), vb = (N % 4 == 0) && aligned16(B);
   const int64_t mn = (int64_t)M * N;
   float *dst = splits == 1 ? C : partials;
   const dim3 grid(tiles, splits);
   if (splits == 1 && accumulate)
-    BNS_GEMM_LAUNCH(false, false, 3, grid, M, N, K, A, M, B, N, dst, N, chunk, va, vb, nullptr, 1.f, nullptr, k_dev, Dropout{});
+    BNS_GEMM_LAUNCH(false, false, 3, grid, M, N, K, A, M_half, B, N, dst, N, chunk, va, vb, nullptr, 1.f, nullptr, k_dev, Dropout{}, A2, M_half, nullptr, 0);
   else
-    BNS_GEMM_LAUNCH(false, false, 0, grid, M, N, K, A, M, B, N, dst, N, chunk, va, vb, nullptr, 1.f, nullptr, k_dev, Dropout{});
+    BNS_GEMM_LAUNCH(false, false, 0, grid, M, N, K, A, M_half, B, N, dst, N, chunk, va, vb, nullptr, 1.f, nullptr, k_dev, Dropout{}, A2, M_half, nullptr, 0);
   // grouped, fixed-order reduction: partials -> level 2 -> ... -> C
   float *cur = partials;
   float *nxt = partials + (size_t)splits * mn;

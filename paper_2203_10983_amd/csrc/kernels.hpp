@@ -135,6 +135,14 @@ struct Dropout {
 // m_dev (nullable): device-side row count, *m_dev <= M; rows past it are not touched.
 hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
                    bool relu, bool accumulate, const Dropout &drop, const int32_t *m_dev, hipStream_t s);
+// C[M,N] = [A1 | A2] B with A1, A2 [M,K_half] and B [2 K_half, N] (the concat update of the mean
+// aggregator layer, Section 2), then optional ReLU / dropout.  Needs K_half % 16 == 0.
+hipError_t gemm_nn_concat(int32_t M, int32_t N, int32_t K_half, const float *A1, const float *A2,
+                          const float *B, float *C, bool relu, const Dropout &drop, hipStream_t s);
+// [C1 | C2] = alpha * A[M,K] B[2 N_half,K]^T, C1 and C2 dense [M,N_half].  Needs N_half % 64 == 0.
+bool gemm_nt_pair_supported(int32_t N_half);
+hipError_t gemm_nt_pair(int32_t M, int32_t N_half, int32_t K, const float *A, const float *B, float *C1,
+                        float *C2, float alpha, hipStream_t s);
 // inv[i] = deg[i] > 1 ? 1 / (deg[i] - 1) : 0   (deg counts the self-loop)
 hipError_t degree_inverse(const int32_t *deg, int32_t n, float *inv, hipStream_t s);
 // C[M,N] = alpha * A[M,K] B[N,K]^T.  mask_src (nullable, [M,N]): C is zeroed where mask_src <= 0.
@@ -148,6 +156,12 @@ int32_t splitk_splits(int32_t M, int32_t N, int32_t K);
 // partial buffer is still sized by splitk_splits(M, N, K)).
 hipError_t gemm_tn_splitk(int32_t M, int32_t N, int32_t K, const float *A, const float *B,
                           float *C, float *partials, bool accumulate, const int32_t *k_dev, hipStream_t s);
+// C[2 M, N] = [A | A2]^T B with A, A2 [K, M] (weight gradient of the concat update); needs M % 128 == 0
+// and partials sized by splitk_splits(2 M, N, K).
+bool gemm_tn_concat_supported(int32_t M_half);
+hipError_t gemm_tn_splitk_concat(int32_t M, int32_t N, int32_t K, const float *A, const float *A2, const float *B,
+                                 float *C, float *partials, bool accumulate, const int32_t *k_dev,
+                                 hipStream_t s);
 
 // ---- loss.hip (Algorithm 1, loss step) ---------------------------------------------------------
 constexpr int kLossBlocks = 8192;  // partials: scratch f32[kLossBlocks]

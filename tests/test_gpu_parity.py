@@ -249,9 +249,9 @@ def test_train_step_end_to_end(case):
         H_below = c.X if l == 1 else view(pkg.VIEW_H, l - 1, torch.float32).view(P.n_in, d_in).clone()
         c.ctx.gcn_layer_bwd(l, p, g, None if l == L else H_l, A_l, H_below, c.W[l - 1], dWl, dH_in, dh)
         torch.cuda.synchronize()
-        assert rel_err(dW[l - 1].cpu().numpy(), dWl.cpu().numpy()) <= 5e-5, f"dW[{l}] vs chained layers"
+        assert rel_err(dW[l - 1].cpu().numpy(), dWl.cpu().numpy()) <= 1e-4, f"dW[{l}] vs chained layers"
         if l > 1:
-            assert rel_err(dhalo[l - 1][:n_u].cpu().numpy(), dh[:n_u].cpu().numpy()) <= 5e-5, \
+            assert rel_err(dhalo[l - 1][:n_u].cpu().numpy(), dh[:n_u].cpu().numpy()) <= 1e-4, \
                 f"dhalo[{l - 1}] vs chained layers"
         g = dH_in
 
