@@ -166,7 +166,9 @@ bns_status bns_train_step(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
  * recorded step n_epochs times on `stream` without synchronising.  Every pointer passed at capture
  * time (and the arrays they name) must stay valid and in place until the graph is replaced by a
  * new capture or the context is destroyed.  With lr > 0 the weights are updated in place, i.e.
- * n replays run n epochs of Algorithm 1.  Event brackets (bns_profile_enable) are not recorded. */
+ * n replays run n epochs of Algorithm 1.  Event brackets (bns_profile_enable) are not recorded.
+ * The dropout rate, the input-aggregate cache and the layer plans in effect at capture time are
+ * part of the recording: change them (bns_set_dropout, bns_cache_input_aggregate) and capture again. */
 bns_status bns_graph_capture(bns_ctx *ctx, uint64_t seed, uint32_t first_epoch, double p, const float *X,
                              const float *const *halo_h, const void *labels, float *const *W,
                              float *const *dW, float *const *dhalo, float *loss, float lr,
