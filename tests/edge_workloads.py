@@ -30,6 +30,16 @@ def no_boundary():
     return _finish("edge-no-boundary", part, [12, 8, 4], 0, 11)
 
 
+def no_boundary_wide():
+    """Empty boundary set again, large and wide enough that the first (hidden) layer, 256 -> 64, is run
+    update first: its ReLU then sits in the aggregate's store and no boundary product exists."""
+    n = 20000
+    src = np.repeat(np.arange(n), 4)
+    dst = (src + np.tile([-2, -1, 1, 2], n)) % n
+    part = partition_from_entries(3, n, src, dst, np.zeros(0, np.int64), np.zeros(0, np.int64))
+    return _finish("edge-no-boundary-wide", part, [256, 64, 4], 0, 17)
+
+
 def star():
     """One inner hub adjacent to every inner node (a row of 3000 entries: many segments) and one
     boundary hub adjacent to every inner node (a transposed row far longer than a segment), plus
@@ -77,4 +87,4 @@ def wide_odd():
     return _finish("edge-wide-odd", part, [602, 130, 66, 9], 0, 15)
 
 
-EDGE = {"e-nobd": no_boundary, "e-star": star, "e-starw": star_wide, "e-single": single_node, "e-wide": wide_odd}
+EDGE = {"e-nobd": no_boundary, "e-nobdw": no_boundary_wide, "e-star": star, "e-starw": star_wide, "e-single": single_node, "e-wide": wide_odd}
