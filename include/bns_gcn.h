@@ -71,7 +71,8 @@ typedef struct {
 
 typedef struct {
   int32_t n_layers;     /* L >= 1                                                          */
-  const int32_t *dims;  /* host int32[L+1]: d_0 .. d_L (layer l maps d_{l-1} -> d_l)       */
+  const int32_t *dims;  /* host int32[L+1]: d_0 .. d_L (layer l maps d_{l-1} -> d_l); each
+                           1..2048 if a multiple of 4, ..1024 if even, ..512 if odd       */
   int32_t loss_kind;    /* 0: softmax cross-entropy, labels dev int32[n_in] in [0, d_L); a
                               negative label marks a node outside the training set (the
                               splits of Table 2): no loss term, zero gradient

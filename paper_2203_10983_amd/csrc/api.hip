@@ -98,8 +98,11 @@ bool valid_desc(const bns_partition_desc *p, const bns_model_desc *m) {
   if (p->e_in + p->e_bd != p->nnz0) return false;
   if (m->n_layers < 1 || (m->loss_kind != 0 && m->loss_kind != 1)) return false;
   if (m->layer_kind != 0 && m->layer_kind != 1) return false;
-  for (int l = 0; l <= m->n_layers; ++l)
-    if (m->dims[l] < 1 || m->dims[l] > 2048) return false;
+  for (int l = 0; l <= m->n_layers; ++l) {
+    // the aggregate holds a row in at most 8 pieces of 64 lanes x (4, 2 or 1) floats
+    const int d = m->dims[l], cap = d % 4 == 0 ? 2048 : d % 2 == 0 ? 1024 : 512;
+    if (d < 1 || d > cap) return false;
+  }
   return true;
 }
 

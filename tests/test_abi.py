@@ -50,10 +50,14 @@ def test_workspace_bytes_is_host_arithmetic(pkg):
     pd2, md2, _k = _descs(pkg, n_in=1000, n_halo=500, nnz0=9000, e_in=8000, e_bd=1000, dims=(64, 32, 8))
     assert lib.bns_workspace_bytes(C.byref(pd2), C.byref(md2)) > small
     # inconsistent entry counts, bad sizes, bad loss kind -> 0
-    for bad in (dict(nnz0=5), dict(n_in=0), dict(n_halo=-1), dict(loss=2), dict(dims=(8, 0))):
+    for bad in (dict(nnz0=5), dict(n_in=0), dict(n_halo=-1), dict(loss=2), dict(dims=(8, 0)),
+                dict(dims=(2052, 8)), dict(dims=(1026, 8)), dict(dims=(8, 513))):   # widths past the kernels' reach
         pdb, mdb, _k = _descs(pkg, **bad)
         assert lib.bns_workspace_bytes(C.byref(pdb), C.byref(mdb)) == 0
     assert lib.bns_workspace_bytes(None, C.byref(md)) == 0
+    for ok in ((2048, 8), (1022, 8), (8, 511)):
+        pdo, mdo, _k = _descs(pkg, dims=ok)
+        assert lib.bns_workspace_bytes(C.byref(pdo), C.byref(mdo)) > 0
 
 
 def test_int32_overflow_is_reported(pkg):
@@ -87,6 +91,10 @@ def test_null_context_is_rejected_everywhere(pkg):
     assert lib.bns_gcn_layer_fwd(None, 1, 0.5, None, None, None, None, None, 1, None) == 1
     assert lib.bns_gcn_layer_bwd(None, 1, 0.5, None, None, None, None, None, None, None, None, None) == 1
     assert lib.bns_train_step(None, 1, 0, 0.5, None, None, None, None, None, None, None, 0.0, None) == 1
+    assert lib.bns_graph_capture(None, 1, 0, 0.5, None, None, None, None, None, None, None, 0.0, None) == 1
+    assert lib.bns_graph_replay(None, 1, None) == 1
+    assert lib.bns_set_dropout(None, 0.5) == 1
+    assert lib.bns_layer_plan(None, 1) == -1
     assert lib.bns_cache_input_aggregate(None, None, None) == 1
     assert lib.bns_profile_enable(None, 0, 0) == 1
     assert lib.bns_last_error(None) == b"null context"
