@@ -87,4 +87,11 @@ def wide_odd():
     return _finish("edge-wide-odd", part, [602, 130, 66, 9], 0, 15)
 
 
-EDGE = {"e-nobd": no_boundary, "e-nobdw": no_boundary_wide, "e-star": star, "e-starw": star_wide, "e-single": single_node, "e-wide": wide_odd}
+def widest():
+    """The widest rows the aggregate kernels take in each of their three load widths: 2048 (16-byte
+    loads), 1022 (8-byte), 511 (4-byte), i.e. eight passes of 64 lanes each."""
+    w = wide_odd()
+    return _finish("edge-widest", w.part, [2048, 1022, 511, 3], 0, 18)
+
+
+EDGE = {"e-nobd": no_boundary, "e-max": widest, "e-nobdw": no_boundary_wide, "e-star": star, "e-starw": star_wide, "e-single": single_node, "e-wide": wide_odd}
