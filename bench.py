@@ -171,14 +171,17 @@ def main():
                 "unit": "TFLOP/s", "frac": achieved / FP32_MFMA_PEAK_TFLOPS, "traffic": None,
                 "launches_per_step": launches[dom], "avg_launch_ms": per_step_ms[dom] / max(launches[dom], 1),
                 "algorithmic_flops_per_step": fl}
-    # HBM-side bytes per launch from the committed rocprofv3 PMC run of this workload, if there is one
+    # HBM-side bytes per launch from the committed rocprofv3 PMC summary of this workload, if there is one
+    # (its "bench-traffic:" line)
+    src = os.path.join("profiles", f"train_step_config{w.cfg}_hbm_traffic.md")
     try:
-        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
-            tr = json.load(fh)
-        if tr["workload"].startswith(f"config {w.cfg}:") and abs(tr["p"] - p) < 1e-12:
+        with open(os.path.join(ROOT, src)) as fh:
+            line = [ln for ln in fh if ln.strip().startswith("bench-traffic:")][-1]
+        tr = json.loads(line.split("bench-traffic:", 1)[1])
+        if tr["workload"].startswith(f"config {w.cfg}:") and abs(tr["p"] - p) < 1e-12 and kind == 0:
             roof["traffic"] = tr["bytes_per_launch"].get(dom)
-            roof["traffic_source"] = tr["source"]
-    except (OSError, KeyError, ValueError):
+            roof["traffic_source"] = src
+    except (OSError, KeyError, ValueError, IndexError):
         pass
     classes = {
         "spmm_fwd_GBps": fwd_bytes / (per_step_ms["spmm_fwd"] * 1e-3) / 1e9 if per_step_ms["spmm_fwd"] else None,
