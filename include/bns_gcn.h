@@ -187,8 +187,12 @@ bns_status bns_graph_replay(bns_ctx *ctx, int32_t n_epochs, void *stream);
  *                          aggregate thereby gathers at least 2^24 fewer floats) is run as
  *                          P (H W): the products H W and H_U W first, then the aggregate at the
  *                          output width; its backward pass forms the weight gradient as
- *                          [H ; H_U]^T (P^T dZ).  BNS_VIEW_A then holds H W (n_in x d_l).  Not
- *                          used for layer 1 while bns_cache_input_aggregate is in effect.
+ *                          [H ; H_U]^T (P^T dZ).  BNS_VIEW_A then holds H W: n_in rows of d_l
+ *                          floats at a row stride of s floats, where s = d_l rounded up to a
+ *                          multiple of 4 if d_l is not one and s < 128 and s <= d_{l-1} (the
+ *                          aggregate gathers 16 bytes per lane; pad columns are zero), else
+ *                          s = d_l.  Not used for layer 1 while bns_cache_input_aggregate is in
+ *                          effect.
  * bns_gcn_layer_fwd / bns_gcn_layer_bwd always aggregate first (their A_saved is the aggregate). */
 typedef enum { BNS_LAYER_TWO_KERNELS = 0, BNS_LAYER_ONE_KERNEL = 1, BNS_LAYER_UPDATE_FIRST = 2 } bns_layer_plan_kind;
 int32_t bns_layer_plan(const bns_ctx *ctx, int32_t layer);

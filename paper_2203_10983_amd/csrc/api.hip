@@ -92,6 +92,15 @@ bool update_first_shape(int layer_kind, int d_in, int d_out) {
   return layer_kind == 0 && (int64_t)d_out * 4 <= (int64_t)d_in * 3;
 }
 
+// Row stride of an operand that is gathered at the output width d_out of a layer: a narrow width
+// that is not a multiple of 4 is padded to one (the aggregate then reads 16 bytes per lane and
+// several neighbours per load instruction) as long as the padded rows fit the buffers, which are
+// sized for the input width.
+int gather_stride(int d_in, int d_out) {
+  const int ld = (d_out + 3) & ~3;
+  return (d_out % 4 != 0 && ld < 128 && ld <= d_in) ? ld : d_out;
+}
+
 bool valid_desc(const bns_partition_desc *p, const bns_model_desc *m) {
   if (!p || !m || !m->dims) return false;
   if (p->n_in < 1 || p->n_halo < 0 || p->nnz0 < p->n_in || p->e_in < p->n_in || p->e_bd < 0) return false;
@@ -125,7 +134,7 @@ size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, La
     if (m->layer_kind == 1)  // [A | H]^T dZ as one product of twice the height
       part_max = std::max(part_max, 2 * mn * (size_t)splitk_splits(2 * m->dims[l], m->dims[l + 1], p->n_in));
     if (update_first_shape(m->layer_kind, m->dims[l], m->dims[l + 1])) {
-      d_first_max = std::max<size_t>(d_first_max, m->dims[l + 1]);
+      d_first_max = std::max<size_t>(d_first_max, gather_stride(m->dims[l], m->dims[l + 1]));
       if (p->n_halo > 0)
         part_max = std::max(part_max, mn * (size_t)splitk_splits(m->dims[l], m->dims[l + 1], p->n_halo));
     }
@@ -259,6 +268,7 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
   const int d_in = ctx->dims[layer - 1], d_out = ctx->dims[layer];
   const bool sage = ctx->layer_kind == 1;
   if (update_first) {
+    const int ld = gather_stride(d_in, d_out);  // row stride of H W and H_U W
     {
       PhaseTimer t(ctx, BNS_PHASE_GATHER, s);
       BNS_TRY("halo_gather", halo_gather(halo_h, ctx->cur_kept, ctx->cur_n_kept, B, ctx->ws.dis_halo, halo_scale(p),
@@ -266,15 +276,15 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
     }
     {
       PhaseTimer t(ctx, BNS_PHASE_GEMM_FWD, s);
-      BNS_TRY("gemm_nn(inner)", gemm_nn(n_in, d_out, d_in, H_in, W, A_saved, false, false, Dropout{}, nullptr, s));
+      BNS_TRY("gemm_nn(inner)", gemm_nn(n_in, d_out, d_in, H_in, W, A_saved, false, false, Dropout{}, nullptr, s, ld));
       if (B > 0)
         BNS_TRY("gemm_nn(boundary)", gemm_nn(B, d_out, d_in, ctx->ws.Hu, W, ctx->ws.Hu2, false, false, Dropout{},
-                                             ctx->cur_n_kept, s));
+                                             ctx->cur_n_kept, s, ld));
     }
     PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
-    BNS_TRY("spmm_fwd", spmm_fwd(ctx->ws.plan_f, n_in, d_out, ctx->cur_row_ptr, ctx->cur_col_idx, ctx->ws.dis_in,
+    BNS_TRY("spmm_fwd", spmm_fwd(ctx->ws.plan_f, n_in, ld, ctx->cur_row_ptr, ctx->cur_col_idx, ctx->ws.dis_in,
                                  ctx->ws.dis_in, A_saved, ctx->ws.Hu2, ctx->ws.spmm_partials, H_out, SpmmRowPart{},
-                                 false, relu, s));
+                                 false, relu, s, d_out));
     BNS_TRY("dropout_inplace", dropout_inplace(n_in, d_out, H_out, dropout_of(ctx, layer, relu), s));
     return BNS_OK;
   }
@@ -344,10 +354,16 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
     float *G_in = ctx->ws.G1, *G_halo = B > 0 ? ctx->ws.Hu2 : nullptr;
     {  // G = P^T dZ at the output width, inner rows and kept boundary rows
       PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
-      BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_out, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
+      const int ld = gather_stride(d_in, d_out);
+      const float *dZ_g = dZ;
+      if (ld != d_out) {  // the gathered operand with padded rows
+        BNS_TRY("pad_rows", pad_rows(n_in, d_out, ld, dZ, ctx->ws.G2, s));
+        dZ_g = ctx->ws.G2;
+      }
+      BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, ld, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
                                    ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_in, ctx->ws.dis_halo,
-                                   halo_scale(p), dZ, nullptr, nullptr, false, ctx->ws.spmm_partials, G_in, G_halo,
-                                   s));
+                                   halo_scale(p), dZ_g, nullptr, nullptr, false, ctx->ws.spmm_partials, G_in, G_halo,
+                                   s, d_out));
     }
     if (B > 0) {  // the kept boundary features once more, unscaled: G_halo carries the 1/p and degree factors
       PhaseTimer t(ctx, BNS_PHASE_GATHER, s);
@@ -417,10 +433,16 @@ bns_status layer_bwd_impl(bns_ctx *ctx, int layer, double p, const float *dZ, co
     float *G_in = ctx->ws.G1, *G_halo = dhalo ? ctx->ws.Hu : nullptr;
     {
       PhaseTimer t(ctx, BNS_PHASE_SPMM_BWD, s);
-      BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, d_out, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
+      const int ld = gather_stride(d_in, d_out);
+      const float *dZ_g = dZ;
+      if (ld != d_out) {  // the gathered operand with padded rows
+        BNS_TRY("pad_rows", pad_rows(n_in, d_out, ld, dZ, ctx->ws.G2, s));
+        dZ_g = ctx->ws.G2;
+      }
+      BNS_TRY("spmm_bwd", spmm_bwd(ctx->ws.plan_b, n_in, B, ld, ctx->cur_t_row_ptr, ctx->cur_t_col_idx,
                                    ctx->cur_kept, ctx->cur_n_kept, ctx->ws.dis_in, ctx->ws.dis_in,
-                                   ctx->ws.dis_halo, halo_scale(p), dZ, nullptr, nullptr, false,
-                                   ctx->ws.spmm_partials, G_in, G_halo, s));
+                                   ctx->ws.dis_halo, halo_scale(p), dZ_g, nullptr, nullptr, false,
+                                   ctx->ws.spmm_partials, G_in, G_halo, s, d_out));
     }
     PhaseTimer t(ctx, BNS_PHASE_GEMM_DA, s);
     BNS_TRY("gemm_nt", gemm_nt(n_in, d_in, d_out, G_in, W, dH_in, mask_src, ms, nullptr, s));

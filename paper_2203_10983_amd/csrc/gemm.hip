@@ -247,7 +247,9 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       int col = bn0 + wn + j * 32 + l32;
-      if (col >= N) continue;
+      // a result with padded rows (ldc > N, plain store only): columns N..ldc-1 are cleared
+      const bool pad_col = col >= N;
+      if (pad_col && !(EPI == 0 && C2 == nullptr && col < ldc)) continue;
       float *Cd = C;
       if (C2 && col >= c_split) { Cd = C2; col -= c_split; }  // column tiles never straddle c_split
 #pragma unroll
@@ -270,7 +272,7 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
               if (drop.scale != 0.f) x = (uint64_t)u[rr] < drop.threshold ? x * drop.scale : 0.f;
             }
             if (EPI == 2) x = mask_src[(size_t)row * ldc + col] > 0.f ? x * alpha : 0.f;
-            if (EPI == 0) x *= alpha;
+            if (EPI == 0) x = pad_col ? 0.f : x * alpha;
             Cd[(size_t)row * ldc + col] = x;
           }
         }
@@ -296,16 +298,19 @@ static inline unsigned n_tiles(int M, int N, int bn) {
   } while (0)
 
 hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   bool relu, bool accumulate, const Dropout &drop, const int32_t *m_dev, hipStream_t s) {
+                   bool relu, bool accumulate, const Dropout &drop, const int32_t *m_dev, hipStream_t s,
+                   int32_t ldc) {
+  if (ldc == 0) ldc = N;
+  if (ldc < N) return hipErrorInvalidValue;
   const int bn = pick_bn(N);
   const unsigned tiles = n_tiles(M, N, bn);
   if (tiles == 0) return hipSuccess;
   const bool va = (K % 4 == 0) && aligned16(A), vb = (N % 4 == 0) && aligned16(B);
   const dim3 grid(tiles, 1);
-  if (accumulate && relu) BNS_GEMM_LAUNCH(true, false, 4, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop, nullptr, 0, nullptr, 0);
-  else if (accumulate) BNS_GEMM_LAUNCH(true, false, 3, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop, nullptr, 0, nullptr, 0);
-  else if (relu) BNS_GEMM_LAUNCH(true, false, 1, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop, nullptr, 0, nullptr, 0);
-  else BNS_GEMM_LAUNCH(true, false, 0, grid, M, N, K, A, K, B, N, C, N, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop, nullptr, 0, nullptr, 0);
+  if (accumulate && relu) BNS_GEMM_LAUNCH(true, false, 4, grid, M, N, K, A, K, B, N, C, ldc, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop, nullptr, 0, nullptr, 0);
+  else if (accumulate) BNS_GEMM_LAUNCH(true, false, 3, grid, M, N, K, A, K, B, N, C, ldc, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop, nullptr, 0, nullptr, 0);
+  else if (relu) BNS_GEMM_LAUNCH(true, false, 1, grid, M, N, K, A, K, B, N, C, ldc, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop, nullptr, 0, nullptr, 0);
+  else BNS_GEMM_LAUNCH(true, false, 0, grid, M, N, K, A, K, B, N, C, ldc, K, va, vb, nullptr, 1.f, m_dev, nullptr, drop, nullptr, 0, nullptr, 0);
   return hipGetLastError();
 }
 

@@ -97,7 +97,13 @@ struct SpmmRowPart {
 hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
                     const int32_t *col_idx, const float *w_col, const float *row_scale,
                     const float *H_in, const float *Hu, float *partials, float *A,
-                    const SpmmRowPart &part, bool long_rows_only, bool relu, hipStream_t s);
+                    const SpmmRowPart &part, bool long_rows_only, bool relu, hipStream_t s,
+                    int32_t d_store = 0);
+// d_store (spmm_fwd and spmm_bwd; 0 = d): the sources and partial sums have rows of d floats of which
+// only the first d_store count (rows padded to a multiple of 4 floats so that a narrow odd width is
+// gathered with 16-byte loads); the outputs are dense [., d_store].  Then d < 128, no mask, no init.
+// pad_rows makes such a padded copy (pad columns zero).
+hipError_t pad_rows(int32_t n_rows, int32_t d, int32_t ld, const float *src, float *dst, hipStream_t s);
 // Aggregate and update of one GCN layer in one kernel (Eq. 1 then Eq. 2): a workgroup aggregates 64
 // rows into LDS (and stores them to A, which the backward pass needs), then multiplies the tile by
 // W on the matrix cores while other workgroups of the same compute unit keep gathering.  Rows cut
@@ -118,7 +124,7 @@ hipError_t spmm_bwd(const SegPlan &plan, int32_t n_in, int32_t n_halo, int32_t d
                     const int32_t *n_kept, const float *w_col, const float *row_scale,
                     const float *dis_halo, float s_halo, const float *dA, const float *mask_src,
                     const float *init, bool skip_self, float *partials, float *dH_in, float *dhalo,
-                    hipStream_t s);
+                    hipStream_t s, int32_t d_store = 0);
 
 // ---- gemm.hip (Eq. 2 and its backward; fp32 MFMA) ----------------------------------------------
 // Dropout on a hidden layer's output (training set-up of Section 4): element (row, col) is kept iff
@@ -133,8 +139,10 @@ struct Dropout {
 // C[M,N] = A[M,K] B[K,N] (+ the previous C if accumulate), then optional ReLU (followed by dropout
 // when drop.scale != 0).
 // m_dev (nullable): device-side row count, *m_dev <= M; rows past it are not touched.
+// ldc: row stride of C (0 = N); without relu / accumulate the columns N..ldc-1 are set to zero.
 hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
-                   bool relu, bool accumulate, const Dropout &drop, const int32_t *m_dev, hipStream_t s);
+                   bool relu, bool accumulate, const Dropout &drop, const int32_t *m_dev, hipStream_t s,
+                   int32_t ldc = 0);
 // C[M,N] = [A1 | A2] B with A1, A2 [M,K_half] and B [2 K_half, N] (the concat update of the mean
 // aggregator layer, Section 2), then optional ReLU / dropout.  Needs K_half % 16 == 0.
 hipError_t gemm_nn_concat(int32_t M, int32_t N, int32_t K_half, const float *A1, const float *A2,

@@ -20,7 +20,7 @@ namespace bns {
 
 // Measured on gfx950: the same code runs 3-6 % slower as soon as the wavefront needs more than 96
 // scalar registers (seven 16-register granules instead of six), so the budget is pinned.
-template <int VEC, int MAXCH, int LPR>
+template <int VEC, int MAXCH, int LPR, bool NARROW = false>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96))) spmm_kernel(const SpmmArgs a) {
   using V = typename Vec<VEC>::T;
   const int lane = lane_id();
@@ -68,7 +68,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96))) spmm
   if (g != 0) {
     // only the first lane group holds the folded sums
   } else if (nseg == 1) {
-    finish_row<VEC, MAXCH>(a, row, sl, nvec, d_off, acc);
+    finish_row<VEC, MAXCH, NARROW>(a, row, sl, nvec, d_off, acc);
   } else {
     V *part = reinterpret_cast<V *>(a.partials + (size_t)(a.plan.part_ptr[row] + seg) * d + d_off);
 #pragma unroll
@@ -87,7 +87,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96))) spmm
 }
 
 // Rows cut into several segments: add the partial sums in ascending segment order.
-template <int VEC, int MAXCH>
+template <int VEC, int MAXCH, bool NARROW = false>
 __global__ void __launch_bounds__(256) spmm_combine_kernel(const SpmmArgs a) {
   using V = typename Vec<VEC>::T;
   const int lane = lane_id();
@@ -123,7 +123,7 @@ __global__ void __launch_bounds__(256) spmm_combine_kernel(const SpmmArgs a) {
         for (int i = 0; i < VEC; ++i) acc[c][i] += px[i];
       }
   }
-  finish_row<VEC, MAXCH>(a, row, lane, nvec, 0, acc);
+  finish_row<VEC, MAXCH, NARROW>(a, row, lane, nvec, 0, acc);
 }
 
 template <int VEC>
@@ -156,6 +156,19 @@ static hipError_t launch_spmm_vec(const SpmmArgs &a_in, int64_t max_units, hipSt
     const unsigned per = 8 / a.n_slices;
     blocks = (blocks + per - 1) / per * 8;
   }
+  if (a.d_store != a.d) {  // padded sources, dense narrower outputs: d < 128, four floats per lane
+    if constexpr (VEC == 4) {
+#define BNS_SPMM_NARROW(LPR) spmm_kernel<4, 1, LPR, true><<<blocks, 256, 0, s>>>(a)
+      if (nvec <= 4) BNS_SPMM_NARROW(4);
+      else if (nvec <= 8) BNS_SPMM_NARROW(8);
+      else if (nvec <= 16) BNS_SPMM_NARROW(16);
+      else BNS_SPMM_NARROW(32);
+#undef BNS_SPMM_NARROW
+      if (cblocks) spmm_combine_kernel<4, 1, true><<<cblocks, 256, 0, s>>>(a);
+      return hipGetLastError();
+    }
+    return hipErrorInvalidValue;
+  }
 #define BNS_SPMM(MAXCH, LPR) spmm_kernel<VEC, MAXCH, LPR><<<blocks, 256, 0, s>>>(a)
   if (nvec <= 1) BNS_SPMM(1, 1);
   else if (nvec <= 2) BNS_SPMM(1, 2);
@@ -183,6 +196,8 @@ static hipError_t launch_spmm_vec(const SpmmArgs &a_in, int64_t max_units, hipSt
 }
 
 static hipError_t launch_spmm(const SpmmArgs &a, int64_t max_units, hipStream_t s) {
+  if (a.d_store != a.d && (a.d_store < 1 || a.d_store > a.d || a.d >= 128 || a.d % 4 != 0 || a.mask_src || a.init))
+    return hipErrorInvalidValue;  // padded sources: narrow rows without mask or initial value only
   if (a.d % 4 == 0) return launch_spmm_vec<4>(a, max_units, s);
   if (a.d % 2 == 0) return launch_spmm_vec<2>(a, max_units, s);
   return launch_spmm_vec<1>(a, max_units, s);
@@ -191,10 +206,11 @@ static hipError_t launch_spmm(const SpmmArgs &a, int64_t max_units, hipStream_t 
 hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
                     const int32_t *col_idx, const float *w_col, const float *row_scale,
                     const float *H_in, const float *Hu, float *partials, float *A,
-                    const SpmmRowPart &part, bool long_rows_only, bool relu, hipStream_t s) {
+                    const SpmmRowPart &part, bool long_rows_only, bool relu, hipStream_t s, int32_t d_store) {
   SpmmArgs a = spmm_fwd_args(plan, n_in, d, row_ptr, col_idx, w_col, row_scale, H_in, Hu, partials, A, part);
   a.multi_only = long_rows_only;
   a.relu = relu;
+  if (d_store > 0) a.d_store = d_store;
   return launch_spmm(a, plan.n_seg, s);
 }
 
@@ -203,10 +219,10 @@ hipError_t spmm_bwd(const SegPlan &plan, int32_t n_in, int32_t n_halo, int32_t d
                     const int32_t *n_kept, const float *w_col, const float *row_scale,
                     const float *dis_halo, float s_halo, const float *dA, const float *mask_src,
                     const float *init, bool skip_self, float *partials, float *dH_in, float *dhalo,
-                    hipStream_t s) {
+                    hipStream_t s, int32_t d_store) {
   SpmmArgs a{};
   const bool halo_rows = dhalo && n_halo > 0;
-  a.plan = plan; a.n_extra_dev = halo_rows ? n_kept : nullptr; a.d = d;
+  a.plan = plan; a.n_extra_dev = halo_rows ? n_kept : nullptr; a.d = d; a.d_store = d_store > 0 ? d_store : d;
   a.row_ptr = t_row_ptr; a.col_idx = t_col_idx; a.n_split = n_in;
   a.src0 = dA; a.src1 = nullptr; a.w_col = w_col; a.partials = partials;
   a.out0 = dH_in; a.out1 = dhalo; a.out_scale0 = row_scale; a.mask_src = mask_src;
@@ -279,6 +295,26 @@ hipError_t build_seg_plan(int32_t n_rows, int64_t nnz, const int32_t *row_ptr, S
   plan->n_multi = tot[2];
   plan->avg_len = n_rows > 0 ? (int32_t)(nnz / n_rows) : 0;
   return hipSuccess;
+}
+
+// ------------------------------------------------------------------------------------------
+// Copy of a dense [n_rows, d] matrix with the rows padded by zeros to ld floats (ld a multiple of
+// 4), so that an aggregate over a narrow odd width can gather with 16-byte loads.
+__global__ void __launch_bounds__(256)
+pad_rows_kernel(int64_t total, int32_t d, int32_t ld, const float *__restrict__ src, float *__restrict__ dst) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int64_t r = i / ld;
+  const int c = (int)(i - r * ld);
+  dst[i] = c < d ? src[r * d + c] : 0.f;
+}
+
+hipError_t pad_rows(int32_t n_rows, int32_t d, int32_t ld, const float *src, float *dst, hipStream_t s) {
+  if (ld < d || d < 1) return hipErrorInvalidValue;
+  const int64_t total = (int64_t)n_rows * ld;
+  if (total == 0) return hipSuccess;
+  pad_rows_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(total, d, ld, src, dst);
+  return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------

@@ -23,7 +23,7 @@ __device__ __forceinline__ void vec_fma(float (&acc)[VEC], float w, const typena
 struct SpmmArgs {
   SegPlan plan;                // static segmentation of rows 0..n_split-1
   const int32_t *n_extra_dev;  // nullable: *n_extra_dev further single-segment rows follow (kept boundary)
-  int32_t d;
+  int32_t d;                   // floats per gathered row = row stride of src0, src1 and the partial sums
   const int32_t *row_ptr, *col_idx;
   int32_t n_split;             // columns < n_split read src0 (weight w_col[c]); others src1 (weight 1)
   const float *src0, *src1, *w_col;
@@ -47,6 +47,9 @@ struct SpmmArgs {
   int32_t n_slices, d_slice;
   bool multi_only;             // work units = segments of the multi-segment rows only
   bool relu;                   // rows < n_split: max(., 0) after the scale (update-first layers)
+  // columns stored per output row = row stride of out0 / out1; less than d when the sources are
+  // padded to a multiple of 4 floats (then no mask, no init, no slices; read by the NARROW kernels only)
+  int32_t d_store;
 };
 
 // Argument block of the forward aggregate (the transposed pass fills its own).
@@ -55,7 +58,7 @@ inline SpmmArgs spmm_fwd_args(const SegPlan &plan, int32_t n_in, int32_t d, cons
                               const float *H_in, const float *Hu, float *partials, float *A,
                               const SpmmRowPart &part) {
   SpmmArgs a{};
-  a.plan = plan; a.n_extra_dev = nullptr; a.d = d;
+  a.plan = plan; a.n_extra_dev = nullptr; a.d = d; a.d_store = d;
   a.row_ptr = row_ptr; a.col_idx = col_idx; a.n_split = n_in;
   a.src0 = H_in; a.src1 = Hu; a.w_col = w_col; a.partials = partials;
   a.out0 = A; a.out1 = nullptr; a.out_scale0 = row_scale; a.mask_src = nullptr;
@@ -68,11 +71,12 @@ inline SpmmArgs spmm_fwd_args(const SegPlan &plan, int32_t n_in, int32_t d, cons
 
 // Scale, optional ReLU mask and store of one finished row slice held as acc[c][i].
 // lds_row (nullable): the finished values are also written there, element iv*VEC+i at lds_row[iv*VEC+i].
-template <int VEC, int MAXCH>
+// NARROW: the sources are padded (d_store < d), the output rows are dense with d_store columns.
+template <int VEC, int MAXCH, bool NARROW = false>
 __device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, int nvec, int d_off,
                                            float (&acc)[MAXCH][VEC], float *lds_row = nullptr) {
   using V = typename Vec<VEC>::T;
-  const int d = a.d;
+  const int d = a.d, ds = NARROW ? (int)a.d_store : d;
   float scale;
   float *out;
   const float *mask = nullptr;
@@ -80,13 +84,13 @@ __device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, i
   if (row < a.n_split) {
     if (a.init) init = a.init + (size_t)row * d + d_off;
     scale = a.out_scale0 ? a.out_scale0[row] : 1.f;
-    out = a.out0 + (size_t)row * d + d_off;
+    out = a.out0 + (size_t)row * ds + d_off;
     if (a.mask_src) mask = a.mask_src + (size_t)row * d + d_off;
   } else {
     if (a.out1 == nullptr) return;
     const int r = row - a.n_split;
     scale = a.dis_halo ? a.s_halo * a.dis_halo[a.kept_ids[r]] : a.s_halo;
-    out = a.out1 + (size_t)r * d + d_off;
+    out = a.out1 + (size_t)r * ds + d_off;
   }
 #pragma unroll
   for (int c = 0; c < MAXCH; ++c) {
@@ -114,7 +118,13 @@ __device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, i
 #pragma unroll
         for (int i = 0; i < VEC; ++i) po[i] = pm[i] > 0.f ? po[i] : 0.f;
       }
-      reinterpret_cast<V *>(out)[iv] = o;
+      if constexpr (!NARROW) {
+        reinterpret_cast<V *>(out)[iv] = o;
+      } else {  // padded sources: the output rows are dense and hold the first ds columns
+#pragma unroll
+        for (int i = 0; i < VEC; ++i)
+          if (iv * VEC + i < ds) out[iv * VEC + i] = po[i];
+      }
       if (lds_row) {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) lds_row[iv * VEC + i] = po[i];

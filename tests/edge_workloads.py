@@ -40,6 +40,24 @@ def no_boundary_wide():
     return _finish("edge-no-boundary-wide", part, [256, 64, 4], 0, 17)
 
 
+def narrow_first():
+    """Output widths that are not multiples of 4 on a graph big enough for an update-first hidden
+    layer: 512 -> 101 is run as P (H W) with the rows of H W padded to 104 floats (the aggregate
+    gathers 16 bytes per lane and stores dense 101-wide rows, ReLU included), 101 -> 7 aggregates
+    first at the odd width 101 and takes the padded gather (8 floats) in its backward pass.  A few
+    hundred boundary nodes, each shared by several inner nodes, and one inner hub of 600 entries."""
+    n = 20000
+    src = np.repeat(np.arange(n), 4)
+    dst = (src + np.tile([-2, -1, 1, 2], n)) % n
+    hub = np.arange(1, 600)
+    src = np.concatenate([src, np.zeros(599, np.int64), hub])
+    dst = np.concatenate([dst, hub, np.zeros(599, np.int64)])
+    src_bd = np.arange(0, n, 3)
+    dst_gid = 7_000_000_000 + (src_bd * 37) % 500
+    part = partition_from_entries(2, n, src, dst, src_bd, dst_gid, halo_full_degree=lambda g, inc: inc + 2)
+    return _finish("edge-narrow-first", part, [512, 101, 7], 0, 19)
+
+
 def star():
     """One inner hub adjacent to every inner node (a row of 3000 entries: many segments) and one
     boundary hub adjacent to every inner node (a transposed row far longer than a segment), plus
@@ -94,4 +112,4 @@ def widest():
     return _finish("edge-widest", w.part, [2048, 1022, 511, 3], 0, 18)
 
 
-EDGE = {"e-nobd": no_boundary, "e-max": widest, "e-nobdw": no_boundary_wide, "e-star": star, "e-starw": star_wide, "e-single": single_node, "e-wide": wide_odd}
+EDGE = {"e-nobd": no_boundary, "e-max": widest, "e-nobdw": no_boundary_wide, "e-narrow": narrow_first, "e-star": star, "e-starw": star_wide, "e-single": single_node, "e-wide": wide_odd}

@@ -32,7 +32,7 @@ FULL = [(2, 1, [1.0, 0.1, 0.01], 0), (3, 1, [0.1], 0), (4, 1, [0.1], 0), (5, 1, 
 # degenerate shapes (tests/edge_workloads.py): empty boundary, hub rows, one node, odd widths
 EDGES = [("e-nobd", 1, [0.5, 1.0], 0), ("e-star", 1, [0.5, 0.0, 1.0], 1), ("e-single", 1, [0.5, 0.0, 1.0], 2),
          ("e-wide", 1, [0.5], 3), ("e-starw", 1, [0.5, 0.0, 1.0], 4),
-         ("e-nobdw", 1, [0.5], 5), ("e-max", 1, [0.5], 6)]
+         ("e-nobdw", 1, [0.5], 5), ("e-max", 1, [0.5], 6), ("e-narrow", 1, [0.5, 1.0], 7)]
 # the same matrix for the GraphSAGE-mean layer (layer_kind 1), thinner
 SAGE = [(1, 1, [0.1, 1.0, 0.0], 0), ("e-star", 1, [0.5], 1), ("e-wide", 1, [0.5], 3), (2, 16, [0.1], 1),
         (3, 32, [0.1], 2), (4, 16, [0.1], 3), (5, 1, [0.1], 0)]
@@ -99,6 +99,12 @@ class _Case:
 def case(request):
     cfg, scale, p, epoch, kind = request.param
     return _Case.get(cfg, scale, kind), p, epoch
+
+
+def _update_first_row_stride(d_in, d_out):
+    """Row stride of BNS_VIEW_A for an update-first layer, as the header states it."""
+    ld = (d_out + 3) // 4 * 4
+    return ld if (d_out % 4 != 0 and ld < 128 and ld <= d_in) else d_out
 
 
 def _oracle_backward_with_device_ties(ref, H_device, w, P, p, kind, drop_scale=1.0, band_rel=1e-5):
@@ -223,8 +229,11 @@ def test_train_step_end_to_end(case):
     plans = [None] + [c.ctx.layer_plan(l) for l in range(1, L + 1)]
     for l in range(1, L + 1):
         H = view(pkg.VIEW_H, l, torch.float32).cpu().numpy().reshape(P.n_in, w.dims[l])
-        if plans[l] == pkg.LAYER_UPDATE_FIRST:   # P (H W): the A view holds H W
-            T = view(pkg.VIEW_A, l, torch.float32)[:P.n_in * w.dims[l]].cpu().numpy().reshape(P.n_in, w.dims[l])
+        if plans[l] == pkg.LAYER_UPDATE_FIRST:   # P (H W): the A view holds H W, rows padded for the gather
+            ld = _update_first_row_stride(w.dims[l - 1], w.dims[l])
+            T = view(pkg.VIEW_A, l, torch.float32)[:P.n_in * ld].cpu().numpy().reshape(P.n_in, ld)
+            assert not T[:, w.dims[l]:].any(), "pad columns of H W must stay zero"
+            T = T[:, :w.dims[l]]
             worst = max(worst, assert_close(T, ref["H"][l - 1] @ w.W[l - 1].astype(np.float64), f"H[{l - 1}] W[{l}]"))
         else:
             A = view(pkg.VIEW_A, l, torch.float32).cpu().numpy().reshape(P.n_in, w.dims[l - 1])
