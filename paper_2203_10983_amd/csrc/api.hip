@@ -40,6 +40,7 @@ struct Layout {
   uint64_t *ballots;
   int32_t *kpos, *hlen;
   float *Hu, *Hu2, *G0, *G1, *G2, *partials, *loss_partials;  // Hu2: boundary rows at the output width
+  int2 *halo_rec;  // per kept boundary node: (boundary index, weight) for the aggregates that read the rows in place
   float *inv_deg;            // 1 / (full-graph degree) of the inner nodes, for the mean aggregator
   SegPlan plan_f, plan_b;   // segmentation of the static CSR and of the transposed inner block
   int32_t *seg_tmp_a, *seg_tmp_b;
@@ -155,6 +156,7 @@ size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, La
   w.hlen = c.take<int32_t>(B + 1);
   w.Hu = c.take<float>(B * d_in_max);
   w.Hu2 = c.take<float>(B * d_first_max);
+  w.halo_rec = c.take<int2>(B + 1);
   w.G0 = c.take<float>(n_in * d_max);
   w.G1 = c.take<float>(n_in * d_max);
   w.G2 = c.take<float>(n_in * d_max);
@@ -289,12 +291,15 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
     return BNS_OK;
   }
   {
-    // GCN: rows pre-scaled by (1/p) d~^-1/2; mean aggregator: by 1/p only
+    // The aggregate reads the kept boundary rows where the caller holds them; it only needs, per
+    // kept node, the row index and the weight S_uu = 1/p (GCN: times d~^-1/2).  A gathered, scaled
+    // copy of the rows would cost a read and a write of every kept row on top of the same reads.
     PhaseTimer t(ctx, BNS_PHASE_GATHER, s);
-    BNS_TRY("halo_gather", halo_gather(halo_h, ctx->cur_kept, ctx->cur_n_kept, B,
-                                       sage ? nullptr : ctx->ws.dis_halo, halo_scale(p), d_in, ctx->ws.Hu, s));
+    BNS_TRY("halo_records", halo_records(ctx->cur_kept, ctx->cur_n_kept, B, sage ? nullptr : ctx->ws.dis_halo,
+                                         halo_scale(p), ctx->ws.halo_rec, s));
   }
   SpmmRowPart part;
+  part.halo_rec = B > 0 ? ctx->ws.halo_rec : nullptr;
   part.skip_self = sage;
   if (layer == 1 && ctx->cache_X != nullptr && ctx->cache_X == H_in) {
     // inner neighbours are the same every epoch: their sum is cached, only the kept boundary
@@ -309,19 +314,19 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
     {
       PhaseTimer t(ctx, BNS_PHASE_SPMM_LONG, s);
       BNS_TRY("spmm_fwd(long rows)", spmm_fwd(ctx->ws.plan_f, n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx, w_col,
-                                              row_scale, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part,
+                                              row_scale, H_in, halo_h, ctx->ws.spmm_partials, A_saved, part,
                                               true, false, s));
     }
     PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
     BNS_TRY("spmm_gemm_fwd", spmm_gemm_fwd(ctx->ws.plan_f, n_in, d_in, d_out, ctx->cur_row_ptr, ctx->cur_col_idx,
-                                           w_col, row_scale, H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved,
+                                           w_col, row_scale, H_in, halo_h, ctx->ws.spmm_partials, A_saved,
                                            part, W, H_out, relu, dropout_of(ctx, layer, relu), s));
     return BNS_OK;
   }
   {
     PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
     BNS_TRY("spmm_fwd", spmm_fwd(ctx->ws.plan_f, n_in, d_in, ctx->cur_row_ptr, ctx->cur_col_idx, w_col, row_scale,
-                                 H_in, ctx->ws.Hu, ctx->ws.spmm_partials, A_saved, part, false, false, s));
+                                 H_in, halo_h, ctx->ws.spmm_partials, A_saved, part, false, false, s));
   }
   {
     PhaseTimer t(ctx, BNS_PHASE_GEMM_FWD, s);

@@ -93,7 +93,14 @@ struct SpmmRowPart {
   const int32_t *row_take = nullptr;
   const float *init = nullptr;
   bool skip_self = false;
+  // halo_rec (from halo_records): Hu is then the whole boundary-feature table [n_halo, d] as the
+  // caller holds it; kept node r reads its row halo_rec[r].x with weight as_float(halo_rec[r].y)
+  const int2 *halo_rec = nullptr;
 };
+// rec[r] = (kept_ids[r], s_halo * dis_halo[kept_ids[r]]) for r < *n_kept (dis_halo nullable = 1): what the
+// aggregate needs to read the kept boundary rows where they are instead of a gathered, scaled copy.
+hipError_t halo_records(const int32_t *kept_ids, const int32_t *n_kept, int32_t n_halo, const float *dis_halo,
+                        float s_halo, int2 *rec, hipStream_t s);
 hipError_t spmm_fwd(const SegPlan &plan, int32_t n_in, int32_t d, const int32_t *row_ptr,
                     const int32_t *col_idx, const float *w_col, const float *row_scale,
                     const float *H_in, const float *Hu, float *partials, float *A,

@@ -363,6 +363,24 @@ halo_gather_kernel(const float *__restrict__ halo_h, const int32_t *__restrict__
   }
 }
 
+__global__ void __launch_bounds__(256)
+halo_records_kernel(const int32_t *__restrict__ kept_ids, const int32_t *__restrict__ n_kept,
+                    const float *__restrict__ dis_halo, float s_halo, int2 *__restrict__ rec) {
+  const int n = *n_kept;
+  for (int r = blockIdx.x * 256 + threadIdx.x; r < n; r += gridDim.x * 256) {
+    const int b = kept_ids[r];
+    rec[r] = make_int2(b, __float_as_int(dis_halo ? s_halo * dis_halo[b] : s_halo));
+  }
+}
+
+hipError_t halo_records(const int32_t *kept_ids, const int32_t *n_kept, int32_t n_halo, const float *dis_halo,
+                        float s_halo, int2 *rec, hipStream_t s) {
+  if (n_halo <= 0) return hipSuccess;
+  const unsigned blocks = (unsigned)std::min<int64_t>(((int64_t)n_halo + 255) / 256, 2048);
+  halo_records_kernel<<<blocks, 256, 0, s>>>(kept_ids, n_kept, dis_halo, s_halo, rec);
+  return hipGetLastError();
+}
+
 hipError_t halo_gather(const float *halo_h, const int32_t *kept_ids, const int32_t *n_kept,
                        int32_t n_halo, const float *dis_halo, float s_halo, int32_t d, float *Hu,
                        hipStream_t s) {

@@ -27,6 +27,10 @@ struct SpmmArgs {
   const int32_t *row_ptr, *col_idx;
   int32_t n_split;             // columns < n_split read src0 (weight w_col[c]); others src1 (weight 1)
   const float *src0, *src1, *w_col;
+  // nullable: src1 is the boundary-feature table as the caller holds it (one row per boundary
+  // node) and stacked column n_split + r reads its row halo_rec[r].x with weight
+  // as_float(halo_rec[r].y); else src1 holds the kept rows in kept order, already scaled
+  const int2 *halo_rec;
   float *partials;             // one d-vector per segment of multi-segment rows
   // output rows < n_split: out0 (scale out_scale0[row], optional mask); others: out1
   float *out0, *out1;
@@ -60,7 +64,7 @@ inline SpmmArgs spmm_fwd_args(const SegPlan &plan, int32_t n_in, int32_t d, cons
   SpmmArgs a{};
   a.plan = plan; a.n_extra_dev = nullptr; a.d = d; a.d_store = d;
   a.row_ptr = row_ptr; a.col_idx = col_idx; a.n_split = n_in;
-  a.src0 = H_in; a.src1 = Hu; a.w_col = w_col; a.partials = partials;
+  a.src0 = H_in; a.src1 = Hu; a.w_col = w_col; a.partials = partials; a.halo_rec = part.halo_rec;
   a.out0 = A; a.out1 = nullptr; a.out_scale0 = row_scale; a.mask_src = nullptr;
   a.kept_ids = nullptr; a.dis_halo = nullptr; a.s_halo = 0.f;
   a.row_skip = part.row_skip; a.row_take = part.row_take; a.init = part.init;
@@ -141,6 +145,10 @@ __device__ __forceinline__ void entry_source(const SpmmArgs &a, int row, int c, 
     p = (unsigned long long)(a.src0 + (size_t)c * d + d_off);
     w = a.w_col ? a.w_col[c] : 1.f;
     if (a.skip_self && c == row) w = 0.f;  // the stored self-loop is not a neighbour
+  } else if (a.halo_rec) {
+    const int2 r = a.halo_rec[c - a.n_split];
+    p = (unsigned long long)(a.src1 + (size_t)r.x * d + d_off);
+    w = __int_as_float(r.y);
   } else {
     p = (unsigned long long)(a.src1 + (size_t)(c - a.n_split) * d + d_off);
     w = 1.f;
