@@ -493,7 +493,9 @@ bns_status build_impl(bns_ctx *ctx, int32_t *row_ptr, int32_t *col_idx, int32_t 
   BNS_TRY("build_transposed_csr",
           build_transposed_csr(P.n_in, P.n_halo, P.e_in, P.t_in_ptr, P.t_in_col, P.halo_ptr, P.halo_col,
                                ctx->cur_kept, ctx->cur_n_kept, ctx->ws.hlen, ctx->ws.tile_sums,
-                               t_row_ptr, t_col_idx, s));
+                               t_row_ptr, t_col_idx,
+                               // the workspace arrays hold the static rows since bns_create
+                               !(t_row_ptr == ctx->ws.t_row_ptr && t_col_idx == ctx->ws.t_col_idx), true, s));
   ctx->cur_row_ptr = row_ptr;
   ctx->cur_col_idx = col_idx;
   ctx->cur_t_row_ptr = t_row_ptr;
@@ -542,6 +544,11 @@ bns_status bns_create(bns_ctx **out, const bns_partition_desc *part, const bns_m
                                                  ctx->ws.seg_tmp_b, ctx->ws.tile_sums, s));
   BNS_TRY("build_seg_plan(bwd)", build_seg_plan(part->n_in, part->e_in, part->t_in_ptr, &ctx->ws.plan_b, ctx->ws.seg_tmp_a,
                                                  ctx->ws.seg_tmp_b, ctx->ws.tile_sums, s));
+  // the rows of the inner nodes in the workspace's transposed CSR are the same in every epoch
+  BNS_TRY("build_transposed_csr(static rows)",
+          build_transposed_csr(part->n_in, part->n_halo, part->e_in, part->t_in_ptr, part->t_in_col, part->halo_ptr,
+                               part->halo_col, nullptr, nullptr, ctx->ws.hlen, ctx->ws.tile_sums, ctx->ws.t_row_ptr,
+                               ctx->ws.t_col_idx, true, false, s));
   BNS_TRY("set-up sync", hipStreamSynchronize(s));
   return BNS_OK;
 }

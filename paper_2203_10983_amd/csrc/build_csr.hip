@@ -229,10 +229,10 @@ hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
                                 const int32_t *halo_ptr, const int32_t *halo_col,
                                 const int32_t *kept_ids, const int32_t *n_kept, int32_t *hlen,
                                 int32_t *tile_sums, int32_t *t_row_ptr, int32_t *t_col_idx,
-                                hipStream_t s) {
+                                bool static_rows, bool kept_rows, hipStream_t s) {
   // rows of inner nodes never change: the transpose of the inner-inner block (copied by a kernel,
   // so that the whole step stays a plain chain of kernel nodes under graph capture)
-  {
+  if (static_rows) {
     const int64_t n4 = ((int64_t)n_in + 1 + e_in + 3) / 4;
     int64_t blocks = (n4 + kThreads - 1) / kThreads;
     if (blocks > 16384) blocks = 16384;
@@ -241,7 +241,7 @@ hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (n_halo == 0) return hipSuccess;
+  if (n_halo == 0 || !kept_rows) return hipSuccess;
   // rows of kept boundary nodes: their static lists of inner neighbours, in kept order
   kept_len_kernel<<<(n_halo + kThreads - 1) / kThreads, kThreads, 0, s>>>(n_kept, kept_ids,
                                                                          halo_ptr, hlen);

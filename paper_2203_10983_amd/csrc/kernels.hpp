@@ -48,12 +48,15 @@ hipError_t build_sampled_csr(int32_t n_in, int64_t e_in, int64_t e_bd, const Sta
                              const uint64_t *ballots, const int32_t *remap, int32_t *kpos, int32_t *tile_sums,
                              int32_t *row_ptr, int32_t *col_idx, int32_t *nnz, hipStream_t s);
 // hlen: scratch int32[n_halo]; tile_sums: scratch int32[scan_tiles(n_halo)+1].
+// static_rows: write the rows of the inner nodes (the transposed inner-inner block, the same every
+// epoch: a destination that already holds them can skip it); kept_rows: write the rows of the kept
+// boundary nodes.
 hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
                                 const int32_t *t_in_ptr, const int32_t *t_in_col,
                                 const int32_t *halo_ptr, const int32_t *halo_col,
                                 const int32_t *kept_ids, const int32_t *n_kept, int32_t *hlen,
                                 int32_t *tile_sums, int32_t *t_row_ptr, int32_t *t_col_idx,
-                                hipStream_t s);
+                                bool static_rows, bool kept_rows, hipStream_t s);
 
 struct Dropout;  // defined with the GEMMs below
 
