@@ -180,7 +180,7 @@ __global__ void __launch_bounds__(kFThreads, 6) __attribute__((amdgpu_num_sgpr(9
     // C element of (lane, register r): row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32
     const int col = n0 + wn + l32;
     if (col < N) {
-#pragma unroll
+#pragma unroll 1
       for (int q4 = 0; q4 < 4; ++q4) {
         const int row4 = row0 + wm + q4 * 8 + lhi * 4;
         uint32_t u[4] = {0u, 0u, 0u, 0u};
