@@ -18,7 +18,6 @@
 namespace bns {
 
 constexpr int kThreads = 256;
-constexpr int kItems = kScanTile / kThreads;
 
 // ---------------------------------------------------------------------------------- set-up
 __global__ void __launch_bounds__(kThreads)
@@ -103,17 +102,34 @@ __device__ __forceinline__ bool kept_bit(const uint64_t *__restrict__ ballots, i
   return (ballots[b >> 6] >> (b & 63)) & 1ull;
 }
 
+// A tile of kScanTile boundary entries per workgroup; every wavefront owns a contiguous piece of
+// it and walks the piece 64 entries at a time, so that all reads and the kpos writes are
+// consecutive over the lanes.  The keep flags of a pass are one ballot word; positions inside a
+// pass come from the population count of the lower lanes' bits.
+constexpr int kWavesPerBlock = kThreads / kWave;
+constexpr int kPasses = kScanTile / kThreads;  // passes of 64 entries per wavefront
+
 __global__ void __launch_bounds__(kThreads)
 bd_keep_tile_sums_kernel(int64_t e_bd, const int32_t *__restrict__ bd_b,
                          const uint64_t *__restrict__ ballots, int32_t *__restrict__ tile_sums) {
-  const int64_t k0 = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kItems;
+  __shared__ int wave_cnt[kWavesPerBlock];
+  const int lane = lane_id(), wid = threadIdx.x / kWave;
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)wid * (kPasses * kWave);
   int cnt = 0;
 #pragma unroll
-  for (int i = 0; i < kItems; ++i)
-    if (k0 + i < e_bd) cnt += kept_bit(ballots, bd_b[k0 + i]);
-  int total;
-  block_exclusive_scan<kThreads>(cnt, &total);
-  if (threadIdx.x == 0) tile_sums[blockIdx.x] = total;
+  for (int i = 0; i < kPasses; ++i) {
+    const int64_t k = base + i * kWave + lane;
+    const bool kept = k < e_bd && kept_bit(ballots, bd_b[k]);
+    cnt += __popcll(__ballot(kept));
+  }
+  if (lane == 0) wave_cnt[wid] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int total = 0;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) total += wave_cnt[w];
+    tile_sums[blockIdx.x] = total;
+  }
 }
 
 __global__ void __launch_bounds__(kThreads)
@@ -121,31 +137,35 @@ bd_fill_kernel(int32_t n_in, int64_t e_bd, const int32_t *__restrict__ bd_b,
                const int32_t *__restrict__ bd_row, const uint64_t *__restrict__ ballots,
                const int32_t *__restrict__ remap, const int32_t *__restrict__ tile_offsets, const int32_t *__restrict__ inner_ptr,
                int32_t *__restrict__ kpos, int32_t *__restrict__ col_idx) {
-  const int64_t k0 = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kItems;
-  int rank[kItems];
+  __shared__ int wave_cnt[kWavesPerBlock];
+  const int lane = lane_id(), wid = threadIdx.x / kWave;
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)wid * (kPasses * kWave);
+  int b[kPasses];
+  unsigned long long mask[kPasses];
   int cnt = 0;
 #pragma unroll
-  for (int i = 0; i < kItems; ++i) {
-    rank[i] = -1;
-    if (k0 + i < e_bd) {
-      const int b = bd_b[k0 + i];
-      if (kept_bit(ballots, b)) rank[i] = remap[b];
-    }
-    cnt += rank[i] >= 0;
+  for (int i = 0; i < kPasses; ++i) {
+    const int64_t k = base + i * kWave + lane;
+    b[i] = k < e_bd ? bd_b[k] : -1;
+    mask[i] = __ballot(b[i] >= 0 && kept_bit(ballots, b[i]));
+    cnt += __popcll(mask[i]);
   }
-  int total;
-  int run = tile_offsets[blockIdx.x] + block_exclusive_scan<kThreads>(cnt, &total);
+  if (lane == 0) wave_cnt[wid] = cnt;
+  __syncthreads();
+  int run = tile_offsets[blockIdx.x];  // kept boundary entries before this wavefront's piece
+  for (int w = 0; w < wid; ++w) run += wave_cnt[w];
+  const unsigned long long lower = (1ull << lane) - 1ull;
 #pragma unroll
-  for (int i = 0; i < kItems; ++i) {
-    const int64_t k = k0 + i;
+  for (int i = 0; i < kPasses; ++i) {
+    const int64_t k = base + i * kWave + lane;
+    const bool kept = (mask[i] >> lane) & 1ull;
+    const int pos = run + __popcll(mask[i] & lower);
     if (k < e_bd) {
-      kpos[k] = run;
-      if (rank[i] >= 0) {
-        col_idx[inner_ptr[bd_row[k] + 1] + run] = n_in + rank[i];
-        ++run;
-      }
-      if (k == e_bd - 1) kpos[e_bd] = run;
+      kpos[k] = pos;
+      if (kept) col_idx[inner_ptr[bd_row[k] + 1] + pos] = n_in + remap[b[i]];
+      if (k == e_bd - 1) kpos[e_bd] = pos + (kept ? 1 : 0);
     }
+    run += __popcll(mask[i]);
   }
 }
 
