@@ -91,8 +91,11 @@ typedef struct {
 size_t bns_workspace_bytes(const bns_partition_desc *part, const bns_model_desc *model);
 
 /* Creates a context on the current device.  `dev_ws` (256-byte aligned, >= bns_workspace_bytes)
- * must stay valid, like every array named in `part`, until bns_destroy.  Runs the one-off
- * set-up kernels (d~^-1/2, inner/boundary split of the CSR) on `stream` and waits for them. */
+ * must stay valid, like every array named in `part`, until bns_destroy, and belongs to the
+ * context from here on: the set-up leaves tables in it that every later call reads (d~^-1/2, the
+ * inner/boundary split of the CSR, segment plans, the static rows of the transposed CSR), so the
+ * caller must neither write to it nor hand it to a second context.  Runs the one-off set-up
+ * kernels on `stream` and waits for them. */
 bns_status bns_create(bns_ctx **out, const bns_partition_desc *part, const bns_model_desc *model,
                       void *dev_ws, size_t ws_bytes, void *stream);
 void bns_destroy(bns_ctx *ctx);
