@@ -137,6 +137,12 @@ def main():
     bwd_bytes = sum(4 * nnz + 4 * (n_in + n_kept + 1) + 4 * bw[l] * n_in
                     + 4 * bw[l] * (n_in + n_kept) for l in range(2, L + 1))
     fwd_bytes += sum(4 * n_in * dims[l] + 4 * dims[l - 1] * dims[l] for l in fused)
+    # bytes the aggregates ask for when no neighbour row is found in a cache (index + one row per entry + output)
+    e_u = nnz - P.e_in
+    fwd_req = sum(4 * nnz + 4 * fw[l] * nnz + 4 * fw[l] * n_in for l in range(1, L + 1))
+    if not args.no_input_cache:
+        fwd_req += -(4 * nnz + 4 * dims[0] * nnz) + 4 * e_u + 4 * dims[0] * e_u + 4 * dims[0] * n_in
+    bwd_req = sum(4 * nnz + 4 * bw[l] * nnz + 4 * bw[l] * (n_in + n_kept) for l in range(2, L + 1))
     kw = 2 if kind == 1 else 1      # the concat update doubles the depth of every product
     gemm_flops = {"gemm_fwd": sum(2 * kw * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1) if l not in fused),
                   "gemm_dw": sum(2 * kw * n_in * dims[l - 1] * dims[l] for l in range(1, L + 1)),
@@ -157,6 +163,8 @@ def main():
                 "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                 "launches_per_step": launches[dom], "avg_launch_ms": per_step_ms[dom] / max(launches[dom], 1),
                 "algorithmic_bytes_per_step": alg}
+        # the other two readings of the same time: what the kernel asks for without any cache re-use ...
+        roof["requested_GBps"] = (fwd_req if dom == "spmm_fwd" else bwd_req) / (per_step_ms[dom] * 1e-3) / 1e9
         if dom == "spmm_fwd" and fused:
             # per launch: the dominant kernel itself, and the long-row pass that precedes it
             roof["avg_launch_ms"] = fwd_kernel_ms / max(launches[dom], 1)
@@ -181,6 +189,9 @@ def main():
         if tr["workload"].startswith(f"config {w.cfg}:") and abs(tr["p"] - p) < 1e-12 and kind == 0:
             roof["traffic"] = tr["bytes_per_launch"].get(dom)
             roof["traffic_source"] = src
+            # ... and what crossed the L2 <-> fabric interface (above the Infinity Cache) per launch of the kernel
+            if roof["traffic"] and roof.get("avg_launch_ms"):
+                roof["traffic_GBps"] = roof["traffic"] / (roof["avg_launch_ms"] * 1e-3) / 1e9
     except (OSError, KeyError, ValueError, IndexError):
         pass
     classes = {
