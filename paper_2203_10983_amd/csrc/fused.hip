@@ -163,6 +163,9 @@ __global__ void __launch_bounds__(kFThreads, 6) __attribute__((amdgpu_num_sgpr(9
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
     *reinterpret_cast<float4 *>(&Bs[0][bk * kFLdb + bq]) = wv;
     __syncthreads();
+    // a wavefront whose 32 columns all lie past the last one (the tail tile of a width such as
+    // 172) still stages W and keeps the barriers, but issues no products
+    const bool has_cols = n0 + wn < N;
 #pragma unroll 1
     for (int kt = 0; kt < nk; ++kt) {
       const int buf = kt & 1;
@@ -171,9 +174,11 @@ __global__ void __launch_bounds__(kFThreads, 6) __attribute__((amdgpu_num_sgpr(9
       wv = kt + 1 < nk ? load_w(n0, (kt + 1) * kFBk) : load_w(n0 + kFBn, 0);
       const float *as = As + (wm + l32) * kFLda + kt * kFBk + lhi;
       const float *bs = Bs[buf] + lhi * kFLdb + wn + l32;
+      if (has_cols) {
 #pragma unroll
-      for (int kk = 0; kk < kFBk; kk += 2)
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(as[kk], bs[kk * kFLdb], acc, 0, 0, 0);
+        for (int kk = 0; kk < kFBk; kk += 2)
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(as[kk], bs[kk * kFLdb], acc, 0, 0, 0);
+      }
       if (kt + 1 < nk) *reinterpret_cast<float4 *>(&Bs[buf ^ 1][bk * kFLdb + bq]) = wv;
       __syncthreads();
     }
