@@ -164,7 +164,7 @@ __device__ __forceinline__ void gather_batch(unsigned long long p_l, float w_l, 
                                              float (&acc)[MAXCH][VEC]) {
   using V = typename Vec<VEC>::T;
   constexpr int EP = kWave / LPR;  // neighbours walked at once
-  constexpr int UNR = 4;
+  constexpr int UNR = (MAXCH == 1 && LPR >= 32) ? 8 : 4;
   const int lane = lane_id();
   const int g = lane / LPR, sl = lane % LPR;
   const unsigned p_lo = (unsigned)p_l, p_hi = (unsigned)(p_l >> 32);
