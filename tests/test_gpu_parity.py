@@ -412,8 +412,9 @@ def test_training_mask_and_adam(loss_cfg):
     ctx.close()
 
 
-@pytest.mark.parametrize("cfg,scale,kind,cached", [(1, 1, 0, False), (3, 16, 0, True), (3, 16, 1, False)],
-                         ids=["tiny-gcn", "cfg3s16-gcn-cached", "cfg3s16-sage"])
+@pytest.mark.parametrize("cfg,scale,kind,cached", [(1, 1, 0, False), (3, 16, 0, True), (3, 16, 1, False),
+                                                   ("e-narrow", 1, 0, False)],
+                         ids=["tiny-gcn", "cfg3s16-gcn-cached", "cfg3s16-sage", "narrow-gcn"])
 def test_graph_replay_equals_eager_epochs(cfg, scale, kind, cached):
     """Algorithm 1's epoch loop recorded once as a HIP graph: every replay (fresh sample from the
     device-side epoch index, in-place SGD) must give bit for bit what the eager entry point gives
@@ -421,7 +422,7 @@ def test_graph_replay_equals_eager_epochs(cfg, scale, kind, cached):
     import torch
     import paper_2203_10983_amd as pkg
     from bns_inputs.workloads import sage_weights
-    w = make_workload(cfg, scale=scale)
+    w = EDGE[cfg]() if isinstance(cfg, str) else make_workload(cfg, scale=scale)
     if kind == 1:
         w.W = sage_weights(5, w.dims)
     dev = torch.device("cuda:0")
@@ -489,9 +490,10 @@ def test_graph_replay_equals_eager_epochs(cfg, scale, kind, cached):
 
 
 @pytest.mark.parametrize("cfg,scale,kind,q", [(1, 1, 0, 0.5), (1, 1, 1, 0.3), (2, 16, 0, 0.3), (3, 32, 0, 0.5),
-                                              (4, 16, 0, 0.1), (5, 64, 1, 0.5), (5, 1, 0, 0.5)],
+                                              (4, 16, 0, 0.1), (5, 64, 1, 0.5), (5, 1, 0, 0.5),
+                                              ("e-narrow", 1, 0, 0.3)],
                          ids=["tiny-gcn-q0.5", "tiny-sage-q0.3", "cfg2s16-gcn-q0.3", "cfg3s32-gcn-q0.5",
-                              "cfg4s16-gcn-q0.1", "cfg5s64-sage-q0.5", "cfg5-gcn-q0.5"])
+                              "cfg4s16-gcn-q0.1", "cfg5s64-sage-q0.5", "cfg5-gcn-q0.5", "narrow-gcn-q0.3"])
 def test_dropout_against_oracle(cfg, scale, kind, q):
     """Dropout on the hidden activations (training set-up of Section 4): same element draws as the
     oracle (bit-exact zero pattern away from ReLU ties), activations, loss and gradients within
@@ -500,7 +502,7 @@ def test_dropout_against_oracle(cfg, scale, kind, q):
     import torch
     import paper_2203_10983_amd as pkg
     from bns_inputs.workloads import sage_weights
-    w = make_workload(cfg, scale=scale)
+    w = EDGE[cfg]() if isinstance(cfg, str) else make_workload(cfg, scale=scale)
     if kind == 1:
         w.W = sage_weights(77, w.dims)
     P, L = w.part, w.n_layers
