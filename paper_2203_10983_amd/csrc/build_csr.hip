@@ -197,7 +197,10 @@ hipError_t build_sampled_csr(int32_t n_in, int64_t e_in, int64_t e_bd, const Sta
   if (e_bd > 0) {
     const int nb = scan_tiles(e_bd);
     bd_keep_tile_sums_kernel<<<nb, kThreads, 0, s>>>(e_bd, sp.bd_b, ballots, tile_sums);
-    (void)scan_sums_inplace(tile_sums, nb, nullptr, s);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = scan_sums_inplace(tile_sums, nb, nullptr, s);
+    if (e != hipSuccess) return e;
     bd_fill_kernel<<<nb, kThreads, 0, s>>>(n_in, e_bd, sp.bd_b, sp.bd_row, ballots, remap, tile_sums,
                                            sp.inner_ptr, kpos, col_idx);
   }

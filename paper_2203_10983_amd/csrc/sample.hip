@@ -89,7 +89,10 @@ hipError_t sample_boundary(const int64_t *halo_gid, int32_t n_halo, uint64_t see
   sample_flags_kernel<<<nb, kSampleThreads, 0, s>>>(halo_gid, n_halo, (uint32_t)seed,
                                                     (uint32_t)(seed >> 32), epoch, epoch_dev, part_id,
                                                     threshold, ballots, tile_sums);
-  (void)scan_sums_inplace(tile_sums, nb, n_kept, s);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  e = scan_sums_inplace(tile_sums, nb, n_kept, s);
+  if (e != hipSuccess) return e;
   if (n_halo > 0)
     sample_write_kernel<<<nb, kSampleThreads, 0, s>>>(n_halo, ballots, tile_sums, kept_ids, remap);
   return hipGetLastError();
