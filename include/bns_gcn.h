@@ -99,7 +99,10 @@ size_t bns_workspace_bytes(const bns_partition_desc *part, const bns_model_desc 
 bns_status bns_create(bns_ctx **out, const bns_partition_desc *part, const bns_model_desc *model,
                       void *dev_ws, size_t ws_bytes, void *stream);
 void bns_destroy(bns_ctx *ctx);
-const char *bns_last_error(const bns_ctx *ctx); /* never NULL; "" if no error so far */
+const char *bns_last_error(const bns_ctx *ctx); /* never NULL; "" if no error so far.  ctx = NULL: the
+                                                   error text of the latest context-free call
+                                                   (bns_sample_boundary_noalloc) on this thread if
+                                                   it failed, else "null context" */
 
 /* Algorithm 1, selection step: U_i <- each b in B_i kept independently with probability p.
  * keep(b) <=> draw(seed, epoch, part_id, halo_gid[b]) < floor(p * 2^32), where draw is the
@@ -113,6 +116,24 @@ const char *bns_last_error(const bns_ctx *ctx); /* never NULL; "" if no error so
  * allocated until a later bns_sample_boundary / bns_train_step replaces them. */
 bns_status bns_sample_boundary(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p,
                                int32_t *kept_ids, int32_t *remap, int32_t *n_kept, void *stream);
+
+/* The same selection step for callers that cannot allocate device memory and have no workspace to
+ * hand over: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  It needs no context and calls no hipMalloc / hipFree or any routine that allocates:
+ * the scratch of the kernels (one keep bit per boundary node, one count per 2048 nodes) lives in a
+ * fixed array of about 0.5 MB inside the library's device code, of which every GPU the library runs
+ * on holds its own copy until the process ends.  Inputs and outputs are the caller's, with the
+ * meaning and layout of bns_sample_boundary (halo_gid dev int64[n_halo], part_id = the partition id
+ * of the draw); the results are bit-identical to it.  n_halo > BNS_NOALLOC_MAX_HALO ->
+ * BNS_EOVERFLOW; bad p or a null pointer -> BNS_EINVAL; bns_last_error(NULL) has the text.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams,
+ * two threads) race and give wrong results; calls that follow each other on one stream are fine,
+ * nothing has to be cleared in between.  The first call on a device looks up the array's address
+ * (a host-side query, no allocation); make that first call outside a stream capture. */
+#define BNS_NOALLOC_MAX_HALO 4194304 /* 2^22 boundary nodes */
+bns_status bns_sample_boundary_noalloc(const int64_t *halo_gid, int32_t n_halo, int32_t part_id,
+                                       uint64_t seed, uint32_t epoch, double p, int32_t *kept_ids,
+                                       int32_t *remap, int32_t *n_kept, void *stream);
 
 /* Algorithm 1, subgraph step: the node-induced subgraph on V_i u U_i, in canonical CSR form, and
  * its transpose for the backward pass.  Uses the sample of the latest bns_sample_boundary.

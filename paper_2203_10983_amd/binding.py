@@ -15,8 +15,10 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbns_gcn.so")
 
+NOALLOC_MAX_HALO = 1 << 22
+
 EXPORTED = ["bns_workspace_bytes", "bns_create", "bns_destroy", "bns_last_error",
-            "bns_sample_boundary", "bns_build_sampled_csr", "bns_gcn_layer_fwd",
+            "bns_sample_boundary", "bns_sample_boundary_noalloc", "bns_build_sampled_csr", "bns_gcn_layer_fwd",
             "bns_gcn_layer_bwd", "bns_train_step", "bns_graph_capture", "bns_graph_replay", "bns_set_dropout", "bns_layer_plan", "bns_adam_update", "bns_cache_input_aggregate", "bns_ws_view",
             "bns_profile_enable", "bns_profile_read"]
 
@@ -74,6 +76,8 @@ def load_library():
     L.bns_last_error.argtypes = [vp]
     L.bns_sample_boundary.restype = i32
     L.bns_sample_boundary.argtypes = [vp, u64, u32, f64, vp, vp, vp, vp]
+    L.bns_sample_boundary_noalloc.restype = i32
+    L.bns_sample_boundary_noalloc.argtypes = [vp, i32, i32, u64, u32, f64, vp, vp, vp, vp]
     L.bns_build_sampled_csr.restype = i32
     L.bns_build_sampled_csr.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     L.bns_gcn_layer_fwd.restype = i32
@@ -126,6 +130,15 @@ def adam_update(W, dW, m, v, lr, beta1=0.9, beta2=0.999, eps=1e-8, t=1):
                                         eps, t, _stream())
     if st != 0:
         raise BnsError(st, "bns_adam_update")
+
+
+def sample_boundary_noalloc(halo_gid, n_halo, part_id, seed, epoch, p, kept_ids, remap, n_kept):
+    """bns_sample_boundary_noalloc: needs no context and no workspace (fixed scratch inside the library)."""
+    L = load_library()
+    st = L.bns_sample_boundary_noalloc(_ptr(halo_gid), n_halo, part_id, seed, epoch, p, _ptr(kept_ids),
+                                       _ptr(remap), _ptr(n_kept), _stream())
+    if st != 0:
+        raise BnsError(st, L.bns_last_error(None).decode())
 
 
 class Context:

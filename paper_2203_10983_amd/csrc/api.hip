@@ -14,6 +14,8 @@
 
 using namespace bns;
 
+const char *bns_noalloc_last_error();  // noalloc.hip: error text of the context-free calls on this thread
+
 namespace {
 
 constexpr size_t kAlign = 256;
@@ -558,7 +560,11 @@ void bns_destroy(bns_ctx *ctx) {
   delete ctx;
 }
 
-const char *bns_last_error(const bns_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+const char *bns_last_error(const bns_ctx *ctx) {
+  if (ctx) return ctx->err.c_str();
+  const char *e = bns_noalloc_last_error();
+  return e[0] ? e : "null context";
+}
 
 bns_status bns_sample_boundary(bns_ctx *ctx, uint64_t seed, uint32_t epoch, double p, int32_t *kept_ids,
                                int32_t *remap, int32_t *n_kept, void *stream) {

@@ -101,6 +101,22 @@ def test_null_context_is_rejected_everywhere(pkg):
     lib.bns_destroy(None)
 
 
+def test_noalloc_entry_point_checks_its_arguments_on_the_host(pkg):
+    lib = pkg.load_library()
+    f = lib.bns_sample_boundary_noalloc
+    ptr = C.c_void_p(0x10000)
+    assert f(ptr, pkg.NOALLOC_MAX_HALO + 1, 0, 1, 0, 0.5, ptr, ptr, ptr, None) == 2      # EOVERFLOW
+    assert b"BNS_NOALLOC_MAX_HALO" in lib.bns_last_error(None)
+    assert f(ptr, 8, 0, 1, 0, 1.5, ptr, ptr, ptr, None) == 1                             # p outside [0, 1]
+    assert f(ptr, 8, 0, 1, 0, float("nan"), ptr, ptr, ptr, None) == 1
+    assert f(ptr, -1, 0, 1, 0, 0.5, ptr, ptr, ptr, None) == 1
+    assert f(None, 8, 0, 1, 0, 0.5, ptr, ptr, ptr, None) == 1                            # null pointers
+    assert f(ptr, 8, 0, 1, 0, 0.5, ptr, ptr, None, None) == 1
+    assert lib.bns_last_error(None) == b"null pointer"
+    header = open(HEADER).read()
+    assert int(re.search(r"#define BNS_NOALLOC_MAX_HALO (\d+)", header).group(1)) == pkg.NOALLOC_MAX_HALO
+
+
 def test_binding_fails_loudly_without_gpu(pkg):
     import torch
     if torch.cuda.is_available():
