@@ -136,17 +136,21 @@ bns_status bns_sample_boundary_noalloc(const int64_t *halo_gid, int32_t n_halo, 
                                        int32_t *remap, int32_t *n_kept, void *stream);
 
 /* Algorithm 1, subgraph step: the node-induced subgraph on V_i u U_i, in canonical CSR form, and
- * its transpose for the backward pass.  Uses the sample of the latest bns_sample_boundary.
+ * its transpose for the backward pass.
+ *   remap, kept_ids, n_kept: the sample, exactly the three arrays the latest bns_sample_boundary on
+ *             this context filled (that call also left the keep bits in the workspace, which this
+ *             one reads); other pointers -> BNS_EINVAL
  *   row_ptr   dev int32[n_in+1], col_idx dev int32[nnz0] (capacity): inner columns unchanged,
  *             kept boundary column n_in+b renumbered n_in+remap[b], order preserved
  *   t_row_ptr dev int32[n_in+n_halo+1] (first n_in+*n_kept+1 valid), t_col_idx dev int32[nnz0]:
  *             for stacked column u the ascending inner rows holding u
  *   nnz       dev int32[1]
- * The context remembers the four array pointers for the layer calls: the arrays must stay
- * allocated until a later bns_build_sampled_csr / bns_train_step replaces them. */
-bns_status bns_build_sampled_csr(bns_ctx *ctx, int32_t *row_ptr, int32_t *col_idx,
-                                 int32_t *t_row_ptr, int32_t *t_col_idx, int32_t *nnz,
-                                 void *stream);
+ * The layer calls below work on the subgraph of the most recent call: the context keeps the four
+ * array pointers (and those of the sample), so the arrays must stay allocated until a later
+ * bns_build_sampled_csr / bns_train_step replaces them. */
+bns_status bns_build_sampled_csr(bns_ctx *ctx, const int32_t *remap, const int32_t *kept_ids,
+                                 const int32_t *n_kept, int32_t *row_ptr, int32_t *col_idx,
+                                 int32_t *t_row_ptr, int32_t *t_col_idx, int32_t *nnz, void *stream);
 
 /* One layer forward, Eq. 1 then Eq. 2 in the sampled matrix form of Appendix A:
  *   A = [P_VV P_VU] S [H_in ; halo_h[kept_ids]],  S = diag(1 .. 1, 1/p .. 1/p),
@@ -259,7 +263,10 @@ typedef enum {
   BNS_VIEW_T_COL_IDX = 6, /* int32[nnz0]              */
   BNS_VIEW_NNZ = 7,       /* int32[1]                 */
   BNS_VIEW_A = 8,         /* layer l: f32[n_in*d_{l-1}], l = 1..L */
-  BNS_VIEW_H = 9          /* layer l: f32[n_in*d_l],     l = 1..L (H_L = logits) */
+  BNS_VIEW_H = 9,         /* layer l: f32[n_in*d_l],     l = 1..L (H_L = logits) */
+  BNS_VIEW_DZ = 10        /* layer l: f32[n_in*d_l],     l = 1..L: gradient of the loss w.r.t. the
+                             pre-activation of layer l as the backward pass used it (for l < L
+                             already masked by H_l > 0 and scaled by the dropout slope) */
 } bns_view;
 bns_status bns_ws_view(const bns_ctx *ctx, bns_view which, int32_t layer, void **dev_ptr,
                        size_t *bytes);

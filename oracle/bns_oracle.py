@@ -40,7 +40,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libbns_oracle.so")
+# BNS_ORACLE_LIB: another build of the same source (the sanitizer build of oracle/build.py)
+_LIB_PATH = os.environ.get("BNS_ORACLE_LIB") or os.path.join(_HERE, "libbns_oracle.so")
 _lib = None
 
 _i32p = np.ctypeslib.ndpointer(dtype=np.int32, flags="C_CONTIGUOUS")
@@ -321,6 +322,123 @@ def backward_sage(part, sub, A, H, W, dZ_last, p, drop_scale=1.0):
                                                       sub["kept_ids"], s, np.ascontiguousarray(dcat[:, :d_in]))
             dH[l - 1] = dh_nbr + dcat[:, d_in:]
     return dW, dhalo, dH
+
+
+# ---------------------------------------------------------------------------------------------
+# Error-bound companions.  An fp32 implementation of a sum of K products cannot be closer to the
+# exact value than a few units of rounding times the sum of the ABSOLUTE values of its terms, however
+# small the (possibly cancelling) result is.  The functions below return, for one layer given its
+# inputs, that sum of absolute terms S for every output element and the number of terms K, so that a
+# test can hold an fp32 result x to |x - ref| <= rtol * max(|ref|, floor) + c * 2^-24 * sqrt(K) * S.
+# Every weight of the propagation matrix (Appendix A: P_vu > 0, S_uu = 1 or 1/p > 0; the mean
+# aggregator's 1/deg > 0) is positive, so the sum of absolute terms of an aggregate is the same
+# aggregate applied to the absolute values of its input.
+def layer_forward_bounds(part, sub, H_in, halo_h, W, p, layer_kind=0):
+    """-> dict(S_A, K_A, S_Z, K_Z) for A = aggregate(H_in, halo_h) and Z = A W (layer_kind 1:
+    Z = [A | H_in] W).  S_*: f64 arrays shaped like A and Z; K_*: f64[n_in, 1] terms per element."""
+    s = halo_scale(p, sub["kept_ids"].shape[0])
+    agg = aggregate if layer_kind == 0 else aggregate_mean
+    H_abs = np.abs(np.asarray(H_in, dtype=np.float64))
+    S_A = agg(part, sub["row_ptr"], sub["col_idx"], sub["kept_ids"], s, H_abs, np.abs(halo_h))
+    W_abs = np.abs(np.asarray(W, dtype=np.float64))
+    K_A = np.diff(sub["row_ptr"]).astype(np.float64)[:, None]
+    if layer_kind == 0:
+        S_Z = S_A @ W_abs
+        K_Z = K_A + H_abs.shape[1]
+    else:
+        S_Z = np.hstack([S_A, H_abs]) @ W_abs
+        K_Z = K_A + 2 * H_abs.shape[1]
+    return dict(S_A=S_A, K_A=np.maximum(K_A, 1.0), S_Z=S_Z, K_Z=K_Z)
+
+
+def layer_backward_bounds(part, sub, A, H_in, W, dZ, p, layer_kind=0, first_layer=False):
+    """-> dict(S_dW, K_dW, S_dH, K_dH, S_dhalo, K_dhalo) for dW = A^T dZ (layer_kind 1:
+    [A | H_in]^T dZ) and [dH ; dhalo] = S^T P^T (dZ W^T) (layer_kind 1: plus the self half of
+    dZ W^T).  first_layer: only the weight gradient exists."""
+    s = halo_scale(p, sub["kept_ids"].shape[0])
+    dZ_abs = np.abs(np.asarray(dZ, dtype=np.float64))
+    A_abs = np.abs(np.asarray(A, dtype=np.float64))
+    H_abs = np.abs(np.asarray(H_in, dtype=np.float64))
+    n_in, d_in = A_abs.shape
+    left = A_abs if layer_kind == 0 else np.hstack([A_abs, H_abs])
+    out = dict(S_dW=left.T @ dZ_abs, K_dW=float(max(n_in, 1)))
+    if first_layer:
+        return out
+    S_dA = dZ_abs @ np.abs(np.asarray(W, dtype=np.float64)).T
+    d_out = dZ_abs.shape[1]
+    t_len = np.diff(sub["t_row_ptr"]).astype(np.float64)[:, None]
+    if layer_kind == 0:
+        S_dH, S_dhalo = aggregate_bwd(part, sub["t_row_ptr"], sub["t_col_idx"], sub["kept_ids"], s, S_dA)
+    else:
+        S_dH, S_dhalo = aggregate_mean_bwd(part, sub["t_row_ptr"], sub["t_col_idx"], sub["kept_ids"], s,
+                                           np.ascontiguousarray(S_dA[:, :d_in]))
+        S_dH = S_dH + S_dA[:, d_in:]
+    out.update(S_dH=S_dH, K_dH=t_len[:n_in] + d_out + 1, S_dhalo=S_dhalo, K_dhalo=t_len[n_in:] + d_out)
+    return out
+
+
+def step_bounds(part, ref, X, halo_h, W, p, layer_kind=0, dropout=0.0):
+    """The bounds of every layer of ``ref`` = step(...), each taken on the oracle's own inputs of that
+    layer.  -> dict of lists indexed like the results: A, H (index l), dW, dhalo (index l-1 as in
+    step), dH (index l), each entry a pair (S, K)."""
+    L = len(W)
+    sub, ds = ref["sub"], dropout_scale(dropout)
+    out = dict(A=[None] * (L + 1), H=[None] * (L + 1), dW=[None] * L, dhalo=[None] * L, dH=[None] * (L + 1))
+    for l in range(1, L + 1):
+        f = layer_forward_bounds(part, sub, ref["H"][l - 1], halo_h[l - 1], W[l - 1], p, layer_kind)
+        out["A"][l] = (f["S_A"], f["K_A"])
+        out["H"][l] = (f["S_Z"] * (ds if l < L else 1.0), f["K_Z"])
+        dZ = ref["dZ_last"] if l == L else ref["dH"][l] * (ref["H"][l] > 0.0) * ds
+        b = layer_backward_bounds(part, sub, ref["A"][l], ref["H"][l - 1], W[l - 1], dZ, p, layer_kind,
+                                  first_layer=(l == 1))
+        out["dW"][l - 1] = (b["S_dW"], b["K_dW"])
+        if l > 1:
+            out["dH"][l - 1] = (b["S_dH"], b["K_dH"])
+            out["dhalo"][l - 1] = (b["S_dhalo"], b["K_dhalo"])
+    return out
+
+
+def layer_forward(part, sub, H_in, halo_h, W, p, layer_kind=0, relu=True, mask=None, drop_scale=1.0):
+    """One layer of ``forward`` / ``forward_sage`` on a given input -> (A, Z, H): the aggregate, the
+    pre-activation and the output (ReLU iff relu; then ``mask`` (0/1, optional) times drop_scale)."""
+    s = halo_scale(p, sub["kept_ids"].shape[0])
+    H_in = np.asarray(H_in, dtype=np.float64)
+    Wd = np.asarray(W, dtype=np.float64)
+    if layer_kind == 0:
+        a = aggregate(part, sub["row_ptr"], sub["col_idx"], sub["kept_ids"], s, H_in, halo_h)
+        z = a @ Wd
+    else:
+        a = aggregate_mean(part, sub["row_ptr"], sub["col_idx"], sub["kept_ids"], s, H_in, halo_h)
+        z = np.hstack([a, H_in]) @ Wd
+    h = np.maximum(z, 0.0) if relu else z
+    if mask is not None:
+        h = h * mask * drop_scale
+    return a, z, h
+
+
+def layer_backward(part, sub, A, H_in, W, dZ, p, layer_kind=0, first_layer=False):
+    """One layer of ``backward`` / ``backward_sage`` on given inputs (dZ = gradient w.r.t. this layer's
+    pre-activation) -> (dW, dH_in, dhalo): dH_in is the gradient w.r.t. the layer's input before any
+    ReLU mask of the layer below; dH_in and dhalo are None for the first layer."""
+    s = halo_scale(p, sub["kept_ids"].shape[0])
+    dZ = np.asarray(dZ, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    Wd = np.asarray(W, dtype=np.float64)
+    if layer_kind == 0:
+        dW = A.T @ dZ
+        if first_layer:
+            return dW, None, None
+        dH, dhalo = aggregate_bwd(part, sub["t_row_ptr"], sub["t_col_idx"], sub["kept_ids"], s, dZ @ Wd.T)
+        return dW, dH, dhalo
+    H_in = np.asarray(H_in, dtype=np.float64)
+    d_in = H_in.shape[1]
+    dW = np.hstack([A, H_in]).T @ dZ
+    if first_layer:
+        return dW, None, None
+    dcat = dZ @ Wd.T
+    dh_nbr, dhalo = aggregate_mean_bwd(part, sub["t_row_ptr"], sub["t_col_idx"], sub["kept_ids"], s,
+                                       np.ascontiguousarray(dcat[:, :d_in]))
+    return dW, dh_nbr + dcat[:, d_in:], dhalo
 
 
 def sample_and_build(part, seed, epoch, p):

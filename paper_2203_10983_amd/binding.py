@@ -26,7 +26,7 @@ PHASES = ["sample", "build", "gather", "spmm_fwd", "gemm_fwd", "loss", "gemm_dw"
           "spmm_bwd", "sgd", "spmm_long"]
 
 VIEW_KEPT_IDS, VIEW_REMAP, VIEW_N_KEPT, VIEW_ROW_PTR, VIEW_COL_IDX = 0, 1, 2, 3, 4
-VIEW_T_ROW_PTR, VIEW_T_COL_IDX, VIEW_NNZ, VIEW_A, VIEW_H = 5, 6, 7, 8, 9
+VIEW_T_ROW_PTR, VIEW_T_COL_IDX, VIEW_NNZ, VIEW_A, VIEW_H, VIEW_DZ = 5, 6, 7, 8, 9, 10
 LAYER_TWO_KERNELS, LAYER_ONE_KERNEL, LAYER_UPDATE_FIRST = 0, 1, 2
 
 _STATUS = {0: "BNS_OK", 1: "BNS_EINVAL", 2: "BNS_EOVERFLOW", 3: "BNS_EWORKSPACE", 4: "BNS_EHIP"}
@@ -79,7 +79,7 @@ def load_library():
     L.bns_sample_boundary_noalloc.restype = i32
     L.bns_sample_boundary_noalloc.argtypes = [vp, i32, i32, u64, u32, f64, vp, vp, vp, vp]
     L.bns_build_sampled_csr.restype = i32
-    L.bns_build_sampled_csr.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    L.bns_build_sampled_csr.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     L.bns_gcn_layer_fwd.restype = i32
     L.bns_gcn_layer_fwd.argtypes = [vp, i32, f64, vp, vp, vp, vp, vp, i32, vp]
     L.bns_gcn_layer_bwd.restype = i32
@@ -197,8 +197,9 @@ class Context:
         self._check(self._lib.bns_sample_boundary(self._ctx, seed, epoch, p, _ptr(kept_ids), _ptr(remap),
                                                   _ptr(n_kept), _stream()))
 
-    def build_sampled_csr(self, row_ptr, col_idx, t_row_ptr, t_col_idx, nnz):
-        self._check(self._lib.bns_build_sampled_csr(self._ctx, _ptr(row_ptr), _ptr(col_idx),
+    def build_sampled_csr(self, remap, kept_ids, n_kept, row_ptr, col_idx, t_row_ptr, t_col_idx, nnz):
+        self._check(self._lib.bns_build_sampled_csr(self._ctx, _ptr(remap), _ptr(kept_ids), _ptr(n_kept),
+                                                    _ptr(row_ptr), _ptr(col_idx),
                                                     _ptr(t_row_ptr), _ptr(t_col_idx), _ptr(nnz),
                                                     _stream()))
 

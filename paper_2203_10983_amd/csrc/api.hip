@@ -52,6 +52,7 @@ struct Layout {
   int32_t *kept_ids, *remap, *counters;
   int32_t *row_ptr, *col_idx, *t_row_ptr, *t_col_idx;
   std::vector<float *> A, H;  // index 1..L
+  std::vector<float *> dZ;    // index 1..L: gradient w.r.t. the pre-activation of layer l (bns_train_step)
 };
 
 }  // namespace
@@ -188,9 +189,11 @@ size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, La
   w.t_col_idx = c.take<int32_t>(p->nnz0);
   w.A.assign(L + 1, nullptr);
   w.H.assign(L + 1, nullptr);
+  w.dZ.assign(L + 1, nullptr);
   for (size_t l = 1; l <= L; ++l) {
     w.A[l] = c.take<float>(n_in * (size_t)m->dims[l - 1]);
     w.H[l] = c.take<float>(n_in * (size_t)m->dims[l]);
+    w.dZ[l] = c.take<float>(n_in * (size_t)m->dims[l]);
   }
   if (out) *out = w;
   return c.off;
@@ -202,6 +205,9 @@ bns_status fail(bns_ctx *ctx, bns_status st, const std::string &msg) {
 }
 
 bns_status hip_fail(bns_ctx *ctx, const char *what, hipError_t e) {
+  // the runtime also keeps a failed call's code as its "last error": take it away, or the next
+  // launcher's hipGetLastError() would report this failure once more as its own
+  (void)hipGetLastError();
   return fail(ctx, BNS_EHIP, std::string(what) + ": " + hipGetErrorString(e));
 }
 
@@ -575,12 +581,16 @@ bns_status bns_sample_boundary(bns_ctx *ctx, uint64_t seed, uint32_t epoch, doub
   return sample_impl(ctx, seed, epoch, nullptr, p, kept_ids, remap, n_kept, static_cast<hipStream_t>(stream));
 }
 
-bns_status bns_build_sampled_csr(bns_ctx *ctx, int32_t *row_ptr, int32_t *col_idx, int32_t *t_row_ptr,
-                                 int32_t *t_col_idx, int32_t *nnz, void *stream) {
+bns_status bns_build_sampled_csr(bns_ctx *ctx, const int32_t *remap, const int32_t *kept_ids, const int32_t *n_kept,
+                                 int32_t *row_ptr, int32_t *col_idx, int32_t *t_row_ptr, int32_t *t_col_idx,
+                                 int32_t *nnz, void *stream) {
   if (!ctx) return BNS_EINVAL;
   if (!row_ptr || !col_idx || !t_row_ptr || !t_col_idx || !nnz)
     return fail(ctx, BNS_EINVAL, "null output pointer");
   if (!ctx->cur_n_kept) return fail(ctx, BNS_EINVAL, "bns_sample_boundary has not been called");
+  // the keep bits of the latest sample sit in the workspace: the three arrays must be that sample's
+  if (remap != ctx->cur_remap || kept_ids != ctx->cur_kept || n_kept != ctx->cur_n_kept)
+    return fail(ctx, BNS_EINVAL, "remap / kept_ids / n_kept are not the outputs of the latest bns_sample_boundary");
   return build_impl(ctx, row_ptr, col_idx, t_row_ptr, t_col_idx, nnz, static_cast<hipStream_t>(stream));
 }
 
@@ -647,19 +657,20 @@ static bns_status train_step_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, c
   {
     PhaseTimer t(ctx, BNS_PHASE_LOSS, s);
     if (ctx->loss_kind == 0)
-      BNS_TRY("loss_softmax_ce", loss_softmax_ce(n_in, C, w.H[L], static_cast<const int32_t *>(labels), w.G0,
+      BNS_TRY("loss_softmax_ce", loss_softmax_ce(n_in, C, w.H[L], static_cast<const int32_t *>(labels), w.dZ[L],
                                                  w.loss_partials, loss, s));
     else
-      BNS_TRY("loss_sigmoid_bce", loss_sigmoid_bce(n_in, C, w.H[L], static_cast<const uint8_t *>(labels), w.G0,
+      BNS_TRY("loss_sigmoid_bce", loss_sigmoid_bce(n_in, C, w.H[L], static_cast<const uint8_t *>(labels), w.dZ[L],
                                                    w.loss_partials, loss, s));
   }
 
-  // G0 holds dZ of the current layer; the transposed aggregate writes the next dZ back into it,
-  // masked by the activations of the layer below
+  // dZ[l] is the gradient w.r.t. the pre-activation of layer l; the backward pass of layer l writes
+  // dZ[l-1], already masked by the activations of the layer below.  Every layer keeps its own buffer
+  // (BNS_VIEW_DZ), so that each stage of the backward pass can be inspected with its exact inputs.
   for (int l = L; l >= 1; --l) {
     float *dh = (dhalo && l > 1) ? dhalo[l - 1] : nullptr;
-    st = layer_bwd_impl(ctx, l, p, w.G0, w.A[l], l > 1 ? w.H[l - 1] : X, W[l - 1], dW[l - 1],
-                        l > 1 ? w.G0 : nullptr, dh,
+    st = layer_bwd_impl(ctx, l, p, w.dZ[l], w.A[l], l > 1 ? w.H[l - 1] : X, W[l - 1], dW[l - 1],
+                        l > 1 ? w.dZ[l - 1] : nullptr, dh,
                         l > 1 ? w.H[l - 1] : nullptr, layer_plan(ctx, l, X) == BNS_LAYER_UPDATE_FIRST,
                         ctx->part.n_halo > 0 ? halo_h[l - 1] : nullptr, s);
     if (st != BNS_OK) return st;
@@ -688,9 +699,11 @@ bns_status bns_graph_capture(bns_ctx *ctx, uint64_t seed, uint32_t first_epoch, 
   if (ctx->graph_exec) { (void)hipGraphExecDestroy(ctx->graph_exec); ctx->graph_exec = nullptr; }
   uint32_t *epoch_dev = reinterpret_cast<uint32_t *>(ctx->ws.counters + 2);
   BNS_TRY("set_counter", set_counter(epoch_dev, first_epoch, s));
-  const uint32_t saved_mask = ctx->prof.mask;
-  ctx->prof.mask = 0;  // event brackets are not part of the graph
   BNS_TRY("hipStreamBeginCapture", hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+  // event brackets are not part of the graph: the phase timers are off between here and the end
+  // of the capture, and there is no return in between
+  const uint32_t saved_mask = ctx->prof.mask;
+  ctx->prof.mask = 0;
   bns_status st = train_step_impl(ctx, seed, 0, epoch_dev, p, X, halo_h, labels, W, dW, dhalo, loss, lr, stream);
   hipError_t e_bump = st == BNS_OK ? bump_counter(epoch_dev, s) : hipSuccess;
   hipGraph_t graph = nullptr;
@@ -798,9 +811,11 @@ bns_status bns_ws_view(const bns_ctx *ctx, bns_view which, int32_t layer, void *
     case BNS_VIEW_NNZ: *dev_ptr = w.counters + 1; *bytes = 4; break;
     case BNS_VIEW_A:
     case BNS_VIEW_H:
+    case BNS_VIEW_DZ:
       if (layer < 1 || layer > ctx->n_layers) return BNS_EINVAL;
       if (which == BNS_VIEW_A) { *dev_ptr = w.A[layer]; *bytes = 4 * n_in * (size_t)ctx->dims[layer - 1]; }
-      else { *dev_ptr = w.H[layer]; *bytes = 4 * n_in * (size_t)ctx->dims[layer]; }
+      else if (which == BNS_VIEW_H) { *dev_ptr = w.H[layer]; *bytes = 4 * n_in * (size_t)ctx->dims[layer]; }
+      else { *dev_ptr = w.dZ[layer]; *bytes = 4 * n_in * (size_t)ctx->dims[layer]; }
       break;
     default: return BNS_EINVAL;
   }

@@ -71,7 +71,10 @@ extern "C" bns_status bns_sample_boundary_noalloc(const int64_t *halo_gid, int32
   if (!n_kept || (n_halo > 0 && (!halo_gid || !kept_ids || !remap))) return fail(BNS_EINVAL, "null pointer");
   unsigned char *base = nullptr;
   hipError_t e = scratch_address(&base);
-  if (e != hipSuccess) return fail(BNS_EHIP, "hipGetSymbolAddress(scratch): ", hipGetErrorString(e));
+  if (e != hipSuccess) {
+    (void)hipGetLastError();  // do not leave the code behind for the next launcher's hipGetLastError()
+    return fail(BNS_EHIP, "hipGetSymbolAddress(scratch): ", hipGetErrorString(e));
+  }
   // Nothing in the scratch has to start at zero: the first kernel writes every ballot word and
   // every tile count that the later ones read, so what an earlier (larger) call left is never seen.
   uint64_t *ballots = reinterpret_cast<uint64_t *>(base);
@@ -79,6 +82,9 @@ extern "C" bns_status bns_sample_boundary_noalloc(const int64_t *halo_gid, int32
   const uint64_t threshold = (uint64_t)std::floor(p * 4294967296.0);
   e = sample_boundary(halo_gid, n_halo, seed, epoch, nullptr, (uint32_t)part_id, threshold, ballots, tile_sums,
                       kept_ids, remap, n_kept, static_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return fail(BNS_EHIP, "sample_boundary: ", hipGetErrorString(e));
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(BNS_EHIP, "sample_boundary: ", hipGetErrorString(e));
+  }
   return BNS_OK;
 }

@@ -87,7 +87,7 @@ def test_create_rejects_bad_arguments_on_the_host(pkg):
 def test_null_context_is_rejected_everywhere(pkg):
     lib = pkg.load_library()
     assert lib.bns_sample_boundary(None, 1, 0, 0.5, None, None, None, None) == 1
-    assert lib.bns_build_sampled_csr(None, None, None, None, None, None, None) == 1
+    assert lib.bns_build_sampled_csr(None, None, None, None, None, None, None, None, None, None) == 1
     assert lib.bns_gcn_layer_fwd(None, 1, 0.5, None, None, None, None, None, 1, None) == 1
     assert lib.bns_gcn_layer_bwd(None, 1, 0.5, None, None, None, None, None, None, None, None, None) == 1
     assert lib.bns_train_step(None, 1, 0, 0.5, None, None, None, None, None, None, None, 0.0, None) == 1

@@ -90,6 +90,69 @@ def test_calls_out_of_order_are_refused():
     ctx.close()
 
 
+def test_build_refuses_arrays_that_are_not_the_latest_sample(live):
+    """bns_build_sampled_csr reads the keep bits the latest bns_sample_boundary left in the workspace,
+    so it accepts only that call's three arrays: a replaced (re-allocated) array is refused on the
+    host instead of being read."""
+    pkg, torch, w, ctx, t = live
+    P = w.part
+    i32 = dict(dtype=torch.int32, device="cuda:0")
+    new = lambda n: torch.empty(n, **i32)  # noqa: E731
+    kept, remap, n_kept = new(P.n_halo + 1), new(P.n_halo + 1), torch.zeros(1, **i32)
+    out = [new(P.n_in + 1), new(P.nnz0), new(P.n_in + P.n_halo + 1), new(P.nnz0), torch.zeros(1, **i32)]
+    ctx.sample_boundary(SAMPLING_SEED, 0, 0.5, kept, remap, n_kept)
+    ctx.build_sampled_csr(remap, kept, n_kept, *out)
+    torch.cuda.synchronize()
+    nnz = int(out[4][0])
+    assert nnz > P.e_in
+    for bad in ((remap.clone(), kept, n_kept), (remap, kept.clone(), n_kept), (remap, kept, n_kept.clone()),
+                (None, kept, n_kept)):
+        st, msg = _status(pkg, lambda: ctx.build_sampled_csr(*bad, *out))
+        assert st == EINVAL and "latest bns_sample_boundary" in msg
+    # a new sample into new arrays replaces the old ones
+    kept2, remap2, n2 = new(P.n_halo + 1), new(P.n_halo + 1), torch.zeros(1, **i32)
+    ctx.sample_boundary(SAMPLING_SEED, 1, 0.5, kept2, remap2, n2)
+    st, _ = _status(pkg, lambda: ctx.build_sampled_csr(remap, kept, n_kept, *out))
+    assert st == EINVAL
+    ctx.build_sampled_csr(remap2, kept2, n2, *out)
+    torch.cuda.synchronize()
+    sub = orc.sample_and_build(P, SAMPLING_SEED, 1, 0.5)
+    assert int(out[4][0]) == sub["col_idx"].size
+    assert np.array_equal(out[1][:sub["col_idx"].size].cpu().numpy(), sub["col_idx"])
+
+
+def test_failed_capture_leaves_the_phase_timers_on(live):
+    """bns_graph_capture switches the event brackets off while it records; a capture that cannot
+    begin (the stream is already capturing) must not leave them off."""
+    pkg, torch, w, ctx, t = live
+    args = (SAMPLING_SEED, 0, 0.1, t["X"], t["halo_h"], t["labels"], t["W"], t["dW"], None, t["loss"])
+    ctx.profile_enable(0xFFFFFFFF, 256)
+    side = torch.cuda.Stream(device="cuda:0")
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        g.capture_begin(capture_error_mode="relaxed")
+        try:
+            st, msg = _status(pkg, lambda: ctx.graph_capture(*args))
+        finally:
+            try:
+                g.capture_end()
+            except RuntimeError:
+                pass        # the refused nested capture may have invalidated the outer one: it ends either way
+    assert st == 4 and "hipStreamBeginCapture" in msg      # BNS_EHIP
+    torch.cuda.synchronize()
+    ctx.train_step(*args)
+    torch.cuda.synchronize()
+    ph = ctx.profile_read()
+    assert ph["sample"][1] >= 1 and ph["spmm_fwd"][1] >= 1, "phase timers must still record after a failed capture"
+    ctx.profile_enable(0, 0)
+    # and a proper capture still works afterwards
+    with torch.cuda.stream(side):
+        ctx.graph_capture(*args)
+        ctx.graph_replay(1)
+    side.synchronize()
+
+
 def test_short_or_misaligned_workspace_is_refused(live):
     pkg, torch, w, ctx, t = live
     lib = pkg.load_library()

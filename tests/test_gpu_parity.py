@@ -1,17 +1,26 @@
 """GPU parity: the HIP library, called through its C ABI, against the CPU oracle.
 
 Integer results (kept sets, remap, CSR and transposed CSR arrays) must match bit for bit.
-fp32 results must match the fp64 oracle within 1e-4 (metric in parity_util.rel_err).
+fp32 results must match the fp64 oracle within 1e-4 relative (absolute floor 1e-6) plus the
+rounding allowance that the oracle derives per element from the sum of absolute terms (metric and
+its constants: parity_util; the bare 1e-4 / 1e-6 metric is asserted on every element that is not
+small by cancellation, and on the loss).
 
 Three levels per case:
   1. sample_boundary + build_sampled_csr               -> bit-exact
   2. gcn_layer_fwd / gcn_layer_bwd fed with the ORACLE's activations, so both sides take the same
-     ReLU decisions                                     -> every element within tolerance
-  3. train_step end to end: integers bit-exact, forward activations and loss within tolerance;
-     its gradients agree (5e-5) with chaining the layer calls of level 2 on its own activations,
-     are bit-identical between two runs (no atomics), and match the oracle within tolerance
-     whenever the oracle reports no pre-activation within rounding distance of zero (otherwise
-     the ReLU derivative there is not unique and a looser norm-wise bound is asserted).
+     ReLU decisions                                     -> every element within the bounded metric
+     (the primary floating-point check: exact inputs, one layer, a bound that holds for any fp32
+     evaluation order)
+  3. train_step end to end: integers bit-exact; every layer's aggregate and output within the
+     bounded metric of the oracle's layer applied to the step's own previous activation (so the
+     bound is again that of one layer on exact inputs), the activations within 1e-5 (rms) of the
+     oracle's own chain, the loss within the bare metric; its gradients agree with chaining the
+     layer calls of level 2 on its own activations, are bit-identical between two runs (no
+     atomics), and match the oracle's gradients (allowance times the number of chained stages);
+     where pre-activations lie within rounding distance of zero the ReLU derivative is not unique:
+     their number is capped by an assertion, and the comparison is made against the oracle's
+     backward pass with exactly those units switched as on the device.
 """
 import sys
 
@@ -21,23 +30,29 @@ import pytest
 from bns_inputs import SAMPLING_SEED, make_workload
 from oracle import bns_oracle as orc
 from edge_workloads import EDGE
-from parity_util import assert_close, rel_err, strict_rel_err, tie_count
+from parity_util import Report, assert_bare, assert_within, rms_err, tie_cap, tie_count, RMS_TOL
 
 pytestmark = pytest.mark.gpu
 
 # (cfg, scale, p list, epoch).  scale 1 = the full workloads of the benchmark.
 SMALL = [(1, 1, [0.1, 0.0, 1.0, 0.5], 0), (2, 16, [0.1, 1.0], 1), (3, 32, [0.1], 2),
          (4, 16, [0.1, 0.0], 3), (5, 64, [0.1, 0.01], 4)]
-FULL = [(2, 1, [1.0, 0.1, 0.01], 0), (3, 1, [0.1], 0), (4, 1, [0.1], 0), (5, 1, [0.1], 0)]
+FULL = [(2, 1, [1.0, 0.1, 0.01], 0), (3, 1, [0.1, 0.01, 1.0], 0), (4, 1, [0.1, 0.01, 1.0], 0),
+        (5, 1, [0.1, 0.01, 1.0], 0)]
 # degenerate shapes (tests/edge_workloads.py): empty boundary, hub rows, one node, odd widths
 EDGES = [("e-nobd", 1, [0.5, 1.0], 0), ("e-star", 1, [0.5, 0.0, 1.0], 1), ("e-single", 1, [0.5, 0.0, 1.0], 2),
          ("e-wide", 1, [0.5], 3), ("e-starw", 1, [0.5, 0.0, 1.0], 4),
          ("e-nobdw", 1, [0.5], 5), ("e-max", 1, [0.5], 6), ("e-narrow", 1, [0.5, 1.0], 7)]
 # the same matrix for the GraphSAGE-mean layer (layer_kind 1), thinner
 SAGE = [(1, 1, [0.1, 1.0, 0.0], 0), ("e-star", 1, [0.5], 1), ("e-wide", 1, [0.5], 3), (2, 16, [0.1], 1),
-        (3, 32, [0.1], 2), (4, 16, [0.1], 3), (5, 1, [0.1], 0)]
+        (3, 32, [0.1], 2), (4, 16, [0.1], 3), (2, 1, [0.1], 0), (3, 1, [0.1], 0), (4, 1, [0.1], 0), (5, 1, [0.1], 0)]
 CASES = [(c, s, p, e, 0) for (c, s, ps, e) in EDGES + SMALL + FULL for p in ps] + \
         [(c, s, p, e, 1) for (c, s, ps, e) in SAGE for p in ps]
+# Full-size cases that run the integer and the layer-level checks only (the end-to-end checks of the
+# same workload run at p = 0.1), to keep the suite within a few minutes: (cfg, p, layer kind)
+LAYER_LEVEL_ONLY = {(c, p, 0) for c in (3, 4, 5) for p in (0.01, 1.0)}
+# ... and those that skip only the cached-input variant
+NO_CACHED_VARIANT = {(c, 0.1, 1) for c in (2, 3, 4)}
 
 
 def _log(msg):
@@ -87,8 +102,10 @@ class _Case:
         if (p, epoch) not in self.ref:
             self.ref.clear()
             w = self.w
-            self.ref[(p, epoch)] = orc.step(w.part, w.loss_kind, w.X, w.halo_h, w.labels, w.W,
-                                            SAMPLING_SEED, epoch, p, layer_kind=self.kind)
+            r = orc.step(w.part, w.loss_kind, w.X, w.halo_h, w.labels, w.W, SAMPLING_SEED, epoch, p,
+                         layer_kind=self.kind)
+            r["bnd"] = orc.step_bounds(w.part, r, w.X, w.halo_h, w.W, p, layer_kind=self.kind)
+            self.ref[(p, epoch)] = r
         return self.ref[(p, epoch)]
 
     def f32(self, a):
@@ -136,7 +153,8 @@ def _sample_and_build(c, p, epoch):
                col_idx=torch.empty(P.nnz0, **i32), t_row_ptr=torch.empty(P.n_in + P.n_halo + 1, **i32),
                t_col_idx=torch.empty(P.nnz0, **i32), nnz=torch.zeros(1, **i32))
     c.ctx.sample_boundary(SAMPLING_SEED, epoch, p, out["kept"], out["remap"], out["n_kept"])
-    c.ctx.build_sampled_csr(out["row_ptr"], out["col_idx"], out["t_row_ptr"], out["t_col_idx"], out["nnz"])
+    c.ctx.build_sampled_csr(out["remap"], out["kept"], out["n_kept"], out["row_ptr"], out["col_idx"], out["t_row_ptr"],
+                            out["t_col_idx"], out["nnz"])
     torch.cuda.synchronize()
     return out
 
@@ -165,15 +183,17 @@ def test_sample_and_csr_bit_exact(case):
 
 
 def test_layers_with_oracle_activations(case):
-    """Every layer forward and backward on the oracle's inputs: all elements within tolerance."""
+    """Every layer forward and backward on the oracle's inputs: all elements within the bounded metric,
+    all elements that are not small by cancellation within the bare 1e-4 / 1e-6 metric."""
     c, p, epoch = case
     w, P, torch = c.w, c.w.part, c.torch
     _log(f"[test] layers cfg={w.cfg} {w.name} p={p} epoch={epoch}")
     ref = c.oracle(p, epoch)
+    bnd = ref["bnd"]
     bufs = _sample_and_build(c, p, epoch)   # the context points into these: keep them alive
     L = w.n_layers
     n_u = ref["sub"]["kept_ids"].size
-    worst = 0.0
+    rep = Report()
     for l in range(1, L + 1):
         d_in, d_out = w.dims[l - 1], w.dims[l]
         H_in = c.X if l == 1 else c.f32(ref["H"][l - 1])
@@ -181,8 +201,8 @@ def test_layers_with_oracle_activations(case):
         H_out = torch.empty(P.n_in, d_out, dtype=torch.float32, device=c.dev)
         c.ctx.gcn_layer_fwd(l, p, H_in, c.halo_h[l - 1], c.W[l - 1], A, H_out, l < L)
         torch.cuda.synchronize()
-        worst = max(worst, assert_close(A.cpu().numpy(), ref["A"][l], f"A[{l}]"))
-        worst = max(worst, assert_close(H_out.cpu().numpy(), ref["H"][l], f"H[{l}]"))
+        assert_within(A.cpu().numpy(), ref["A"][l], bnd["A"][l], f"A[{l}]", rep)
+        assert_within(H_out.cpu().numpy(), ref["H"][l], bnd["H"][l], f"H[{l}]", rep)
         # backward of the same layer from the oracle's upstream gradient and activations
         dH_out = c.f32(ref["dZ_last"] if l == L else ref["dH"][l])
         H_ref = None if l == L else c.f32(ref["H"][l])
@@ -191,18 +211,119 @@ def test_layers_with_oracle_activations(case):
         dhalo = torch.full((P.n_halo + 1, d_in), 7.0, dtype=torch.float32, device=c.dev) if l > 1 else None
         c.ctx.gcn_layer_bwd(l, p, dH_out, H_ref, c.f32(ref["A"][l]), H_in, c.W[l - 1], dW, dH_in, dhalo)
         torch.cuda.synchronize()
-        worst = max(worst, assert_close(dW.cpu().numpy(), ref["dW"][l - 1], f"dW[{l}]"))
+        assert_within(dW.cpu().numpy(), ref["dW"][l - 1], bnd["dW"][l - 1], f"dW[{l}]", rep)
         if l > 1:
-            worst = max(worst, assert_close(dH_in.cpu().numpy(), ref["dH"][l - 1], f"dH[{l - 1}]"))
+            assert_within(dH_in.cpu().numpy(), ref["dH"][l - 1], bnd["dH"][l - 1], f"dH[{l - 1}]", rep)
             got = dhalo.cpu().numpy()
-            worst = max(worst, assert_close(got[:n_u], ref["dhalo"][l - 1], f"dhalo[{l - 1}]"))
+            assert_within(got[:n_u], ref["dhalo"][l - 1], bnd["dhalo"][l - 1], f"dhalo[{l - 1}]", rep)
             assert np.all(got[n_u:] == 7.0), "rows past the kept count must stay untouched"
-    _log(f"[test]   worst relative error {worst:.2e}")
+    _log("[test]   " + rep.line())
     del bufs
+
+
+def _check_forward_chain(c, ref, p, rep, masks=None, drop_scale=1.0, drift=True):
+    """The activations train_step left in the workspace, layer by layer: A[l] and H[l] against the
+    oracle's layer applied to the step's OWN H[l-1] (exact inputs, so the allowance is that of one
+    layer), and H[l] against the oracle's own chain in the rms sense (drift)."""
+    w, P, torch, pkg = c.w, c.w.part, c.torch, c.pkg
+    L = w.n_layers
+    view = lambda which, layer=0, dt=torch.int32: c.ctx.ws_tensor(which, layer, dt)  # noqa: E731
+    H_dev = [w.X]
+    for l in range(1, L + 1):
+        d_in, d_out = w.dims[l - 1], w.dims[l]
+        H = view(pkg.VIEW_H, l, torch.float32).cpu().numpy().reshape(P.n_in, d_out)
+        mask = None if masks is None or l == L else masks[l]
+        a, z, h = orc.layer_forward(P, ref["sub"], H_dev[l - 1], w.halo_h[l - 1], w.W[l - 1], p, layer_kind=c.kind,
+                                    relu=l < L, mask=mask, drop_scale=drop_scale)
+        b = orc.layer_forward_bounds(P, ref["sub"], H_dev[l - 1], w.halo_h[l - 1], w.W[l - 1], p, layer_kind=c.kind)
+        if c.ctx.layer_plan(l) == pkg.LAYER_UPDATE_FIRST:   # P (H W): the A view holds H W, rows padded for the gather
+            ld = _update_first_row_stride(d_in, d_out)
+            T = view(pkg.VIEW_A, l, torch.float32)[:P.n_in * ld].cpu().numpy().reshape(P.n_in, ld)
+            assert not T[:, d_out:].any(), "pad columns of H W must stay zero"
+            Hp = H_dev[l - 1].astype(np.float64)
+            Wd = w.W[l - 1].astype(np.float64)
+            assert_within(T[:, :d_out], Hp @ Wd, (np.abs(Hp) @ np.abs(Wd), float(d_in)), f"H[{l - 1}] W[{l}]", rep)
+        else:
+            A = view(pkg.VIEW_A, l, torch.float32).cpu().numpy().reshape(P.n_in, d_in)
+            assert_within(A, a, (b["S_A"], b["K_A"]), f"A[{l}]", rep)
+        assert_within(H, h, (b["S_Z"] * (drop_scale if l < L else 1.0), b["K_Z"]), f"H[{l}]", rep)
+        if drift:
+            dr = rms_err(H, ref["H"][l])
+            assert dr <= RMS_TOL * l, f"H[{l}] drifts from the oracle's chain: rms {dr:.2e}"
+        H_dev.append(H)
+    return H_dev
+
+
+def _check_backward_chain(c, ref, p, H_dev, dW, dhalo, n_u, rep, drop_scale=1.0):
+    """The gradients train_step produced, stage by stage: the loss gradient against the oracle's on
+    the step's own logits; dW[l], the masked gradient handed to layer l-1 and dhalo[l-1] against the
+    oracle's backward stage applied to the step's own A[l], H[l-1] and dZ[l] (BNS_VIEW_DZ)."""
+    w, P, torch, pkg = c.w, c.w.part, c.torch, c.pkg
+    L = w.n_layers
+    sub = ref["sub"]
+    view = lambda which, layer: c.ctx.ws_tensor(which, layer, torch.float32).cpu().numpy()  # noqa: E731
+    dZ = [None] + [view(pkg.VIEW_DZ, l).reshape(P.n_in, w.dims[l]) for l in range(1, L + 1)]
+    _, g = orc.loss_and_grad(H_dev[L], w.labels, w.loss_kind)
+    # softmax / sigmoid minus target: at most C + 1 terms of magnitude <= 1
+    assert_within(dZ[L], g, (np.ones_like(g), float(w.dims[L] if w.loss_kind == 0 else 1) + 1.0), "dZ[L]", rep)
+    t_len = np.diff(sub["t_row_ptr"]).astype(np.float64)
+    for l in range(L, 0, -1):
+        d_in = w.dims[l - 1]
+        first = c.ctx.layer_plan(l) == pkg.LAYER_UPDATE_FIRST
+        if first:   # the step never formed this aggregate: its weight gradient is [H ; H_U]^T (P^T dZ)
+            A_l, _, _ = orc.layer_forward(P, sub, H_dev[l - 1], w.halo_h[l - 1], w.W[l - 1], p, layer_kind=c.kind)
+            A_abs = orc.layer_forward_bounds(P, sub, H_dev[l - 1], w.halo_h[l - 1], w.W[l - 1], p, c.kind)["S_A"]
+        else:
+            A_l = view(pkg.VIEW_A, l).reshape(P.n_in, d_in)
+            A_abs = A_l
+        gW, gH, gh = orc.layer_backward(P, sub, A_l, H_dev[l - 1], w.W[l - 1], dZ[l], p, layer_kind=c.kind,
+                                        first_layer=(l == 1))
+        b = orc.layer_backward_bounds(P, sub, A_abs, H_dev[l - 1], w.W[l - 1], dZ[l], p, layer_kind=c.kind,
+                                      first_layer=(l == 1))
+        K_dW = b["K_dW"] + (float(n_u) + (t_len.max() if t_len.size else 0.0) if first else 0.0)
+        assert_within(dW[l - 1].cpu().numpy(), gW, (b["S_dW"], K_dW), f"dW[{l}]", rep)
+        if l > 1:
+            on = (H_dev[l - 1] > 0) * drop_scale
+            assert_within(dZ[l - 1], gH * on, (b["S_dH"] * on, b["K_dH"]), f"dZ[{l - 1}]", rep)
+            if dhalo is not None and dhalo[l - 1] is not None and n_u:
+                assert_within(dhalo[l - 1][:n_u].cpu().numpy(), gh, (b["S_dhalo"], b["K_dhalo"]), f"dhalo[{l - 1}]", rep)
+
+
+def _gradient_drift(ref, H_device, w, P, p, kind, dW, dhalo, n_u, drop_scale=1.0):
+    """rms distance of the step's gradients from the oracle's own chain, per chained stage (asserted
+    <= 1e-5).  A hidden unit whose pre-activation lies within rounding distance of zero may be on on
+    one side and off on the other; there are few of them (their number is capped by an assertion), and
+    for this comparison the oracle's backward pass switches exactly those as the device did."""
+    L = w.n_layers
+    n_hidden = sum(ref["Z"][l].size for l in range(1, L))
+    ties = sum(tie_count(ref["Z"][l]) for l in range(1, L))
+    assert ties <= tie_cap(n_hidden), f"{ties} pre-activations within rounding of zero out of {n_hidden}"
+    want_dW, want_dhalo = ref["dW"], ref["dhalo"]
+    if ties:
+        want_dW, want_dhalo = _oracle_backward_with_device_ties(ref, H_device, w, P, p, kind, drop_scale=drop_scale)
+    drift = 0.0
+    for l in range(1, L + 1):
+        d = rms_err(dW[l - 1].cpu().numpy(), want_dW[l - 1]) / _grad_stages(L, l)
+        if l > 1 and n_u and dhalo is not None:
+            d = max(d, rms_err(dhalo[l - 1][:n_u].cpu().numpy(), want_dhalo[l - 1]) / _grad_stages(L, l))
+        drift = max(drift, d)
+    assert drift <= RMS_TOL, f"gradients drift from the oracle's chain: rms {drift:.2e} per stage"
+    return drift, ties, n_hidden
+
+
+def _grad_stages(L, l):
+    """Layer stages a gradient of layer l went through in fp32: L forward, then L..l backward."""
+    return float(L + (L - l + 1))
+
+
+def _skip_if(c, p, which):
+    if c.key[1] == 1 and (c.key[0], p, c.kind) in which:
+        pytest.skip("full-size case covered at the integer and layer level only")
 
 
 def test_train_step_end_to_end(case):
     c, p, epoch = case
+    _skip_if(c, p, LAYER_LEVEL_ONLY)
     w, P, torch, pkg = c.w, c.w.part, c.torch, c.pkg
     _log(f"[test] train_step cfg={w.cfg} {w.name} p={p} epoch={epoch}")
     ref = c.oracle(p, epoch)
@@ -225,45 +346,15 @@ def test_train_step_end_to_end(case):
     _check_integers(P, ref["sub"], view(pkg.VIEW_KEPT_IDS).cpu().numpy(), view(pkg.VIEW_REMAP).cpu().numpy(),
                     n_kept, view(pkg.VIEW_ROW_PTR).cpu().numpy(), view(pkg.VIEW_COL_IDX).cpu().numpy(),
                     view(pkg.VIEW_T_ROW_PTR).cpu().numpy(), view(pkg.VIEW_T_COL_IDX).cpu().numpy(), nnz)
-    worst = 0.0
-    plans = [None] + [c.ctx.layer_plan(l) for l in range(1, L + 1)]
-    for l in range(1, L + 1):
-        H = view(pkg.VIEW_H, l, torch.float32).cpu().numpy().reshape(P.n_in, w.dims[l])
-        if plans[l] == pkg.LAYER_UPDATE_FIRST:   # P (H W): the A view holds H W, rows padded for the gather
-            ld = _update_first_row_stride(w.dims[l - 1], w.dims[l])
-            T = view(pkg.VIEW_A, l, torch.float32)[:P.n_in * ld].cpu().numpy().reshape(P.n_in, ld)
-            assert not T[:, w.dims[l]:].any(), "pad columns of H W must stay zero"
-            T = T[:, :w.dims[l]]
-            worst = max(worst, assert_close(T, ref["H"][l - 1] @ w.W[l - 1].astype(np.float64), f"H[{l - 1}] W[{l}]"))
-        else:
-            A = view(pkg.VIEW_A, l, torch.float32).cpu().numpy().reshape(P.n_in, w.dims[l - 1])
-            worst = max(worst, assert_close(A, ref["A"][l], f"A[{l}]"))
-        worst = max(worst, assert_close(H, ref["H"][l], f"H[{l}]"))
-    assert abs(float(loss[0]) - ref["loss"]) <= 1e-4 * abs(ref["loss"]), (float(loss[0]), ref["loss"])
+    rep = Report()
+    H_device = _check_forward_chain(c, ref, p, rep)
+    assert_bare(float(loss[0]), ref["loss"], "loss")
 
-    # (a) the layer calls (checked against the oracle above) chained by hand on the step's own
-    # activations, i.e. with the step's own ReLU decisions, reproduce its gradients
-    g = None
-    for l in range(L, 0, -1):
-        d_in, d_out = w.dims[l - 1], w.dims[l]
-        H_l = view(pkg.VIEW_H, l, torch.float32).view(P.n_in, d_out).clone()
-        if plans[l] == pkg.LAYER_UPDATE_FIRST:   # the step never formed this aggregate
-            A_l = c.f32(ref["A"][l])
-        else:
-            A_l = view(pkg.VIEW_A, l, torch.float32).view(P.n_in, d_in).clone()
-        if l == L:  # the oracle's gradient of the loss
-            g = c.f32(ref["dZ_last"])
-        dWl = torch.empty_like(c.W[l - 1])
-        dH_in = torch.empty(P.n_in, d_in, **f32) if l > 1 else None
-        dh = torch.zeros(P.n_halo + 1, d_in, **f32) if l > 1 else None
-        H_below = c.X if l == 1 else view(pkg.VIEW_H, l - 1, torch.float32).view(P.n_in, d_in).clone()
-        c.ctx.gcn_layer_bwd(l, p, g, None if l == L else H_l, A_l, H_below, c.W[l - 1], dWl, dH_in, dh)
-        torch.cuda.synchronize()
-        assert rel_err(dW[l - 1].cpu().numpy(), dWl.cpu().numpy()) <= 1e-4, f"dW[{l}] vs chained layers"
-        if l > 1:
-            assert rel_err(dhalo[l - 1][:n_u].cpu().numpy(), dh[:n_u].cpu().numpy()) <= 1e-4, \
-                f"dhalo[{l - 1}] vs chained layers"
-        g = dH_in
+    # (a) every stage of the step's backward pass against the oracle's stage applied to the step's OWN
+    # inputs of that stage (its activations, and the gradient it kept per layer): exact inputs, so the
+    # allowance is that of one layer
+    rep_b = Report()
+    _check_backward_chain(c, ref, p, H_device, dW, dhalo, n_u, rep_b)
 
     # (b) run-to-run determinism
     dW2, dhalo2, loss2 = run()
@@ -273,27 +364,12 @@ def test_train_step_end_to_end(case):
     for a, b in zip(dhalo[1:], dhalo2[1:]):
         assert torch.equal(a, b)
 
-    # (c) gradients against the oracle
-    ties = sum(tie_count(ref["Z"][l]) for l in range(1, L))
-    errs = [rel_err(dW[l].cpu().numpy(), ref["dW"][l]) for l in range(L)]
-    errs += [rel_err(dhalo[l][:n_u].cpu().numpy(), ref["dhalo"][l]) for l in range(1, L)]
-    strict = max(strict_rel_err(dW[l].cpu().numpy(), ref["dW"][l]) for l in range(L))
-    _log(f"[test]   fwd worst {worst:.2e}; grads worst {max(errs):.2e} (bare-floor metric {strict:.2e}); "
-         f"pre-activations within rounding of zero: {ties}")
-    if ties == 0:
-        assert max(errs) <= 1e-4, errs
-    else:
-        for l in range(L):
-            g_gpu, g_ref = dW[l].cpu().numpy().astype(np.float64), ref["dW"][l]
-            assert np.abs(g_gpu - g_ref).max() <= 2e-2 * np.abs(g_ref).max(), f"dW[{l}] (with ties)"
-        # (d) the oracle's backward pass with the tied ReLUs switched as on the device: no ambiguity left
-        H_device = [None] + [view(pkg.VIEW_H, l, torch.float32).cpu().numpy().reshape(P.n_in, w.dims[l])
-                             for l in range(1, L + 1)]
-        dW2, dhalo2 = _oracle_backward_with_device_ties(ref, H_device, w, P, p, c.kind)
-        errs2 = [rel_err(dW[l].cpu().numpy(), dW2[l]) for l in range(L)]
-        errs2 += [rel_err(dhalo[l][:n_u].cpu().numpy(), dhalo2[l]) for l in range(1, L)]
-        _log(f"[test]   grads against the oracle's backward with tied ReLUs switched as on the device: {max(errs2):.2e}")
-        assert max(errs2) <= 1e-4, errs2
+    # (c) drift of the gradients from the oracle's own chain
+    drift, ties, n_hidden = _gradient_drift(ref, H_device, w, P, p, c.kind, dW, dhalo, n_u)
+    _log(f"[test]   forward stages: {rep.line()}")
+    _log(f"[test]   backward stages: {rep_b.line()}")
+    _log(f"[test]   rms drift of the gradients from the oracle's chain per stage {drift:.2e} "
+         f"({ties} tied units of {n_hidden} switched as on the device)")
     for l in range(1, L):
         assert np.all(dhalo[l][n_u:].cpu().numpy() == 0.0)
 
@@ -302,6 +378,7 @@ def test_train_step_with_cached_input_aggregate(case):
     """Static-inner caching (bns_cache_input_aggregate): layer 1 aggregates only the kept boundary
     tail of each row on top of the cached inner sum; results must still match the oracle."""
     c, p, epoch = case
+    _skip_if(c, p, LAYER_LEVEL_ONLY | NO_CACHED_VARIANT)
     w, P, torch, pkg = c.w, c.w.part, c.torch, c.pkg
     _log(f"[test] cached input aggregate cfg={w.cfg} {w.name} p={p} epoch={epoch}")
     ref = c.oracle(p, epoch)
@@ -309,27 +386,24 @@ def test_train_step_with_cached_input_aggregate(case):
     f32 = dict(dtype=torch.float32, device=c.dev)
     dW = [torch.empty_like(x) for x in c.W]
     loss = torch.zeros(1, **f32)
+    bnd = ref["bnd"]
+    rep = Report()
     c.ctx.cache_input_aggregate(c.X)
     try:
         c.ctx.train_step(SAMPLING_SEED, epoch, p, c.X, c.halo_h, c.labels, c.W, dW, None, loss, 0.0)
         torch.cuda.synchronize()
         assert c.ctx.layer_plan(1) != pkg.LAYER_UPDATE_FIRST    # the cached sum is an aggregate of X
-        for l in range(1, L + 1):
-            H = c.ctx.ws_tensor(pkg.VIEW_H, l, torch.float32).cpu().numpy().reshape(P.n_in, w.dims[l])
-            if c.ctx.layer_plan(l) != pkg.LAYER_UPDATE_FIRST:
-                A = c.ctx.ws_tensor(pkg.VIEW_A, l, torch.float32).cpu().numpy().reshape(P.n_in, w.dims[l - 1])
-                assert_close(A, ref["A"][l], f"A[{l}] (cached)")
-            assert_close(H, ref["H"][l], f"H[{l}] (cached)")
-        assert abs(float(loss[0]) - ref["loss"]) <= 1e-4 * abs(ref["loss"])
-        # the last layer's weight gradient does not pass through any ReLU decision
-        assert_close(dW[L - 1].cpu().numpy(), ref["dW"][L - 1], f"dW[{L}] (cached)")
+        H_device = _check_forward_chain(c, ref, p, rep)
+        assert_bare(float(loss[0]), ref["loss"], "loss (cached)")
+        _check_backward_chain(c, ref, p, H_device, dW, None, ref["sub"]["kept_ids"].size, rep)
         # a different input pointer must not use the cache
         X2 = c.X.clone()
         A1 = torch.empty(P.n_in, w.dims[0], **f32)
         H1 = torch.empty(P.n_in, w.dims[1], **f32)
         c.ctx.gcn_layer_fwd(1, p, X2, c.halo_h[0], c.W[0], A1, H1, L > 1)
         torch.cuda.synchronize()
-        assert_close(A1.cpu().numpy(), ref["A"][1], "A[1] (other pointer, uncached)")
+        assert_within(A1.cpu().numpy(), ref["A"][1], bnd["A"][1], "A[1] (other pointer, uncached)", rep)
+        _log("[test]   " + rep.line())
     finally:
         c.ctx.cache_input_aggregate(None)
 
@@ -337,7 +411,9 @@ def test_train_step_with_cached_input_aggregate(case):
 @pytest.mark.parametrize("kind", [0, 1], ids=["gcn", "sage"])
 def test_sgd_trajectory_on_tiny(kind):
     """Algorithm 1, update step: three epochs of w <- w - lr * g with a fresh sample per epoch.
-    The HIP library and the oracle each follow their own trajectory from the same start."""
+    Each update is checked on its exact inputs (the weights before the step and the gradient the
+    step returned); the HIP library and the oracle each follow their own trajectory from the same
+    start, and the two stay together (losses within the bare metric, weights in the rms sense)."""
     import torch
     import paper_2203_10983_amd as pkg
     from bns_inputs.workloads import sage_weights
@@ -356,15 +432,20 @@ def test_sgd_trajectory_on_tiny(kind):
     lr, p = 2e-3, 0.5
     losses = []
     for epoch in range(3):
+        W_before = [x.cpu().numpy().astype(np.float64) for x in W]
         ctx.train_step(SAMPLING_SEED, epoch, p, X, halo_h, labels, W, dW, None, loss, lr)
         torch.cuda.synchronize()
+        for l in range(len(W)):      # the update itself: two terms, exact inputs
+            g = dW[l].cpu().numpy().astype(np.float64)
+            assert_within(W[l].cpu().numpy(), W_before[l] - lr * g, (np.abs(W_before[l]) + lr * np.abs(g), 2.0),
+                          f"W[{l}] after the update of epoch {epoch}")
         ref = orc.step(w.part, w.loss_kind, w.X, w.halo_h, w.labels, W_ref, SAMPLING_SEED, epoch, p, lr=lr,
                        layer_kind=kind)
         W_ref = ref["W_new"]
         losses.append(float(loss[0]))
-        assert abs(losses[-1] - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+        assert_bare(losses[-1], ref["loss"], f"loss of epoch {epoch}")
         for a, b in zip(W, W_ref):
-            assert_close(a.cpu().numpy(), b, f"weights after epoch {epoch}")
+            assert rms_err(a.cpu().numpy(), b) <= RMS_TOL, f"weights after epoch {epoch} drift from the oracle's"
     assert losses[2] < losses[0]
     ctx.close()
 
@@ -372,7 +453,10 @@ def test_sgd_trajectory_on_tiny(kind):
 @pytest.mark.parametrize("loss_cfg", [1, "bce"], ids=["ce", "bce"])
 def test_training_mask_and_adam(loss_cfg):
     """Nodes (entries) outside the training set carry no loss and no gradient; Adam follows the
-    oracle's fp64 trajectory for four steps."""
+    oracle's fp64 trajectory for four steps.  Every Adam update is checked on its exact inputs (the
+    device's weights, gradient and moments before the call); the step's gradients are checked stage
+    by stage; the two trajectories stay together in the rms sense."""
+    import types
     import torch
     import paper_2203_10983_amd as pkg
     w = make_workload(1) if loss_cfg == 1 else make_workload(4, scale=64)
@@ -394,27 +478,42 @@ def test_training_mask_and_adam(loss_cfg):
     W_ref = [x.astype(np.float64) for x in w.W]
     m_ref = [np.zeros_like(x) for x in W_ref]
     v_ref = [np.zeros_like(x) for x in W_ref]
+    f64 = lambda x: x.cpu().numpy().astype(np.float64)  # noqa: E731
     # eps is taken large enough that a gradient element whose sign is decided by rounding moves its
     # weight by far less than the tolerance (Adam's step is g / (|g| + eps) at t = 1)
     lr, p, eps = 1e-3, 0.5, 1e-2
+    b1, b2 = float(np.float32(0.9)), float(np.float32(0.999))     # the decay rates cross the ABI as floats
+    rep = Report()
     for t in range(1, 5):
         ctx.train_step(SAMPLING_SEED, t, p, X, halo_h, labels, W, dW, None, loss, 0.0)
-        for l in range(len(W)):
-            pkg.adam_update(W[l], dW[l], m[l], v[l], lr, eps=eps, t=t)
         torch.cuda.synchronize()
         ref = orc.step(w.part, w.loss_kind, w.X, w.halo_h, w.labels, W_ref, SAMPLING_SEED, t, p)
-        assert abs(float(loss[0]) - ref["loss"]) <= 1e-4 * abs(ref["loss"])
+        assert_bare(float(loss[0]), ref["loss"], f"loss of step {t}")
+        # the masked loss gradient and every backward stage on the step's own inputs (the weights are the device's)
+        wd = types.SimpleNamespace(**{**vars(w), "W": [x.cpu().numpy() for x in W], "n_layers": w.n_layers})
+        ns = types.SimpleNamespace(w=wd, torch=torch, pkg=pkg, ctx=ctx, kind=0)
+        H_dev = _check_forward_chain(ns, ref, p, rep, drift=False)
+        _check_backward_chain(ns, ref, p, H_dev, dW, None, ref["sub"]["kept_ids"].size, rep)
         for l in range(len(W)):
-            assert_close(dW[l].cpu().numpy(), ref["dW"][l], f"dW[{l}] step {t}")
-            W_ref[l], m_ref[l], v_ref[l] = orc.adam_step(W_ref[l], ref["dW"][l], m_ref[l], v_ref[l], lr, 0.9,
-                                                         0.999, eps, t)
-            assert_close(W[l].cpu().numpy(), W_ref[l], f"W[{l}] after Adam step {t}")
+            assert rms_err(f64(dW[l]), ref["dW"][l]) <= RMS_TOL * t * _grad_stages(len(W), l + 1), f"dW[{l}] step {t}"
+            Wb, mb, vb, g = f64(W[l]), f64(m[l]), f64(v[l]), f64(dW[l])
+            pkg.adam_update(W[l], dW[l], m[l], v[l], lr, beta1=b1, beta2=b2, eps=eps, t=t)
+            torch.cuda.synchronize()
+            Wn, mn, vn = orc.adam_step(Wb, g, mb, vb, lr, b1, b2, eps, t)
+            assert_within(f64(m[l]), mn, (b1 * np.abs(mb) + (1 - b1) * np.abs(g), 2.0), f"m[{l}] step {t}", rep)
+            assert_within(f64(v[l]), vn, (vn, 2.0), f"v[{l}] step {t}", rep)
+            # the step m^ / (sqrt(v^) + eps) is a quotient of a few rounded quantities: four roundings of it
+            assert_within(f64(W[l]), Wn, (np.abs(Wb) + 4.0 * np.abs(Wn - Wb), 2.0), f"W[{l}] after Adam step {t}", rep)
+            W_ref[l], m_ref[l], v_ref[l] = orc.adam_step(W_ref[l], ref["dW"][l], m_ref[l], v_ref[l], lr, b1, b2, eps, t)
+            assert rms_err(f64(W[l]), W_ref[l]) <= RMS_TOL * t, f"W[{l}] after Adam step {t} drifts from the oracle's"
+    _log("[test]   " + rep.line())
     ctx.close()
 
 
 @pytest.mark.parametrize("cfg,scale,kind,cached", [(1, 1, 0, False), (3, 16, 0, True), (3, 16, 1, False),
-                                                   ("e-narrow", 1, 0, False)],
-                         ids=["tiny-gcn", "cfg3s16-gcn-cached", "cfg3s16-sage", "narrow-gcn"])
+                                                   ("e-narrow", 1, 0, False), (5, 1, 0, True), (5, 1, 1, False)],
+                         ids=["tiny-gcn", "cfg3s16-gcn-cached", "cfg3s16-sage", "narrow-gcn", "cfg5-gcn-cached",
+                              "cfg5-sage"])
 def test_graph_replay_equals_eager_epochs(cfg, scale, kind, cached):
     """Algorithm 1's epoch loop recorded once as a HIP graph: every replay (fresh sample from the
     device-side epoch index, in-place SGD) must give bit for bit what the eager entry point gives
@@ -491,9 +590,10 @@ def test_graph_replay_equals_eager_epochs(cfg, scale, kind, cached):
 
 @pytest.mark.parametrize("cfg,scale,kind,q", [(1, 1, 0, 0.5), (1, 1, 1, 0.3), (2, 16, 0, 0.3), (3, 32, 0, 0.5),
                                               (4, 16, 0, 0.1), (5, 64, 1, 0.5), (5, 1, 0, 0.5),
-                                              ("e-narrow", 1, 0, 0.3)],
+                                              ("e-narrow", 1, 0, 0.3), (2, 1, 0, 0.3)],
                          ids=["tiny-gcn-q0.5", "tiny-sage-q0.3", "cfg2s16-gcn-q0.3", "cfg3s32-gcn-q0.5",
-                              "cfg4s16-gcn-q0.1", "cfg5s64-sage-q0.5", "cfg5-gcn-q0.5", "narrow-gcn-q0.3"])
+                              "cfg4s16-gcn-q0.1", "cfg5s64-sage-q0.5", "cfg5-gcn-q0.5", "narrow-gcn-q0.3",
+                              "cfg2-gcn-q0.3"])
 def test_dropout_against_oracle(cfg, scale, kind, q):
     """Dropout on the hidden activations (training set-up of Section 4): same element draws as the
     oracle (bit-exact zero pattern away from ReLU ties), activations, loss and gradients within
@@ -526,33 +626,24 @@ def test_dropout_against_oracle(cfg, scale, kind, q):
     torch.cuda.synchronize()
     ref = orc.step(P, w.loss_kind, w.X, w.halo_h, w.labels, w.W, SAMPLING_SEED, epoch, p, layer_kind=kind,
                    dropout=q)
+    bnd = orc.step_bounds(P, ref, w.X, w.halo_h, w.W, p, layer_kind=kind, dropout=q)
     n_u = ref["sub"]["kept_ids"].size
-    ties = 0
-    for l in range(1, L + 1):
-        H = ctx.ws_tensor(pkg.VIEW_H, l, torch.float32).cpu().numpy().reshape(P.n_in, w.dims[l])
-        assert_close(H, ref["H"][l], f"H[{l}]")
-        if l < L:
-            near = np.abs(ref["Z"][l]) <= 1e-5 * np.abs(ref["Z"][l]).max()
-            ties += tie_count(ref["Z"][l])
-            assert np.array_equal((H > 0)[~near], (ref["H"][l] > 0)[~near]), f"zero pattern of H[{l}]"
-            kept_frac = (ref["H"][l] > 0).sum() / max((ref["Z"][l] > 0).sum(), 1)
-            assert abs(kept_frac - (1 - q)) < 0.05
-    assert abs(float(loss[0]) - ref["loss"]) <= 1e-4 * abs(ref["loss"])
-    errs = [rel_err(dW[l].cpu().numpy(), ref["dW"][l]) for l in range(L)]
-    errs += [rel_err(dhalo[l][:n_u].cpu().numpy(), ref["dhalo"][l]) for l in range(1, L)]
-    _log(f"[test]   grads worst {max(errs):.2e}; ties {ties}")
-    if ties == 0:
-        assert max(errs) <= 1e-4, errs
-    else:
-        # some ReLUs are decided by rounding: the oracle's backward pass with those switched as on the device
-        H_device = [None] + [ctx.ws_tensor(pkg.VIEW_H, l, torch.float32).cpu().numpy().reshape(P.n_in, w.dims[l])
-                             for l in range(1, L + 1)]
-        dW2, dhalo2 = _oracle_backward_with_device_ties(ref, H_device, w, P, p, kind,
-                                                        drop_scale=orc.dropout_scale(q))
-        errs2 = [rel_err(dW[l].cpu().numpy(), dW2[l]) for l in range(L)]
-        errs2 += [rel_err(dhalo[l][:n_u].cpu().numpy(), dhalo2[l]) for l in range(1, L)]
-        _log(f"[test]   grads against the oracle's backward with tied ReLUs switched as on the device: {max(errs2):.2e}")
-        assert max(errs2) <= 1e-4, errs2
+    ds = orc.dropout_scale(q)
+    masks = [None] + [orc.dropout_mask(SAMPLING_SEED, epoch, P.part_id, l, P.n_in, w.dims[l], q) for l in range(1, L)]
+    rep = Report()
+    import types
+    ns = types.SimpleNamespace(w=w, torch=torch, pkg=pkg, ctx=ctx, kind=kind)
+    H_device = _check_forward_chain(ns, ref, p, rep, masks=masks, drop_scale=ds)
+    for l in range(1, L):
+        H = H_device[l]
+        near = np.abs(ref["Z"][l]) <= 1e-5 * np.abs(ref["Z"][l]).max()
+        assert np.array_equal((H > 0)[~near], (ref["H"][l] > 0)[~near]), f"zero pattern of H[{l}]"
+        kept_frac = (ref["H"][l] > 0).sum() / max((ref["Z"][l] > 0).sum(), 1)
+        assert abs(kept_frac - (1 - q)) < 0.05
+    assert_bare(float(loss[0]), ref["loss"], "loss")
+    _check_backward_chain(ns, ref, p, H_device, dW, dhalo, n_u, rep, drop_scale=ds)
+    drift, ties, n_hidden = _gradient_drift(ref, H_device, w, P, p, kind, dW, dhalo, n_u, drop_scale=ds)
+    _log(f"[test]   {rep.line()}; rms drift of the gradients per stage {drift:.2e} ({ties} tied units of {n_hidden})")
 
     # the layer calls: forward of layer 1 and its backward from the oracle's upstream gradient
     i32 = dict(dtype=torch.int32, device=dev)
@@ -561,35 +652,36 @@ def test_dropout_against_oracle(cfg, scale, kind, q):
                 col_idx=torch.empty(P.nnz0, **i32), t_row_ptr=torch.empty(P.n_in + P.n_halo + 1, **i32),
                 t_col_idx=torch.empty(P.nnz0, **i32), nnz=torch.zeros(1, **i32))
     ctx.sample_boundary(SAMPLING_SEED, epoch, p, bufs["kept"], bufs["remap"], bufs["n_kept"])
-    ctx.build_sampled_csr(bufs["row_ptr"], bufs["col_idx"], bufs["t_row_ptr"], bufs["t_col_idx"], bufs["nnz"])
+    ctx.build_sampled_csr(bufs["remap"], bufs["kept"], bufs["n_kept"], bufs["row_ptr"], bufs["col_idx"], bufs["t_row_ptr"],
+                          bufs["t_col_idx"], bufs["nnz"])
     A1 = torch.empty(P.n_in, w.dims[0], **f32)
     H1 = torch.empty(P.n_in, w.dims[1], **f32)
     ctx.gcn_layer_fwd(1, p, X, halo_h[0], W[0], A1, H1, 1)
     torch.cuda.synchronize()
-    assert_close(H1.cpu().numpy(), ref["H"][1], "layer call H[1]")
+    assert_within(H1.cpu().numpy(), ref["H"][1], bnd["H"][1], "layer call H[1]")
     dW1 = torch.empty_like(W[0])
     to32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)  # noqa: E731
     ctx.gcn_layer_bwd(1, p, to32(ref["dH"][1]), to32(ref["H"][1]), to32(ref["A"][1]), X, W[0], dW1, None, None)
     torch.cuda.synchronize()
-    assert_close(dW1.cpu().numpy(), ref["dW"][0], "layer call dW[1]")
+    assert_within(dW1.cpu().numpy(), ref["dW"][0], bnd["dW"][0], "layer call dW[1]")
 
-    if scale > 1 or cfg == 1:   # graph replay: a fresh mask per epoch, bit-identical to eager steps
-        want = []
-        for e in (epoch, epoch + 1):
-            ctx.train_step(SAMPLING_SEED, e, p, X, halo_h, labels, W, dW, dhalo, loss, 0.0)
-            torch.cuda.synchronize()
-            want.append((loss.clone(), [x.clone() for x in dW]))
-        assert not torch.equal(want[0][1][0], want[1][1][0])
-        side = torch.cuda.Stream(device=dev)
-        side.wait_stream(torch.cuda.current_stream())
+    # graph replay: a fresh mask per epoch, bit-identical to eager steps
+    want = []
+    for e in (epoch, epoch + 1):
+        ctx.train_step(SAMPLING_SEED, e, p, X, halo_h, labels, W, dW, dhalo, loss, 0.0)
+        torch.cuda.synchronize()
+        want.append((loss.clone(), [x.clone() for x in dW]))
+    assert not torch.equal(want[0][1][0], want[1][1][0])
+    side = torch.cuda.Stream(device=dev)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ctx.graph_capture(SAMPLING_SEED, epoch, p, X, halo_h, labels, W, dW, dhalo, loss, 0.0)
+    for e in range(2):
         with torch.cuda.stream(side):
-            ctx.graph_capture(SAMPLING_SEED, epoch, p, X, halo_h, labels, W, dW, dhalo, loss, 0.0)
-        for e in range(2):
-            with torch.cuda.stream(side):
-                ctx.graph_replay(1)
-            side.synchronize()
-            assert torch.equal(loss, want[e][0])
-            for a, b in zip(dW, want[e][1]):
-                assert torch.equal(a, b)
+            ctx.graph_replay(1)
+        side.synchronize()
+        assert torch.equal(loss, want[e][0])
+        for a, b in zip(dW, want[e][1]):
+            assert torch.equal(a, b)
     bufs.clear()
     ctx.close()
