@@ -13,7 +13,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libbns_gcn.so")
+# BNS_GCN_LIB: another build of the same library (for A/B measurements of kernel variants)
+LIB_PATH = os.environ.get("BNS_GCN_LIB") or os.path.join(_HERE, "libbns_gcn.so")
 
 NOALLOC_MAX_HALO = 1 << 22
 

@@ -4,9 +4,15 @@
 //   forward   H = A W            gemm_nn : A [M,K] k-contiguous,  B [K,N] n-contiguous
 //   backward  dA = dZ W^T        gemm_nt : A [M,K] k-contiguous,  B [N,K] k-contiguous
 //   backward  dW = A^T dZ        gemm_tn : A [K,M] m-contiguous,  B [K,N] n-contiguous, split K
-// A 256-thread block (4 wavefronts) owns a 128 x BN tile of C.  BN = 128: wavefronts 2x2, each
-// 64x64 as 2x2 MFMA tiles of 32x32.  BN = 64 (chosen when it wastes fewer padded columns, e.g.
-// N = 172, 47, 41): wavefronts 4x1, each 32x64.  Operand tiles of depth 16 are staged through LDS
+// A block owns a 128 x BN tile of C.  BN = 128 with a k-contiguous A (forward product, dZ W^T): 8
+// wavefronts (2 x 4), each 64 x 32 = two 32x32 accumulators; BN = 128 with an m-contiguous A (the
+// split-K weight gradient): 4 wavefronts (2 x 2), each 64 x 64; BN = 64 (chosen when it wastes
+// fewer padded columns, e.g. N = 172, 47, 41): 4 wavefronts (4 x 1), each 32 x 64.  Measured on
+// gfx950: four wavefronts per SIMD with four accumulators each issue matrix instructions at 79 %
+// of the peak rate even with nothing else in the loop, two accumulators each at 98 %; stand-alone
+// the 8-wavefront tile is 10 - 26 % faster than the 4-wavefront one, inside a training step 3 - 8 %
+// (the weight gradient, which streams both operands, lost 1 - 3 % and keeps four wavefronts).
+// Operand tiles of depth 16 are staged through LDS
 // in k-major order (As[k][m], Bs[k][n]) so that an MFMA operand read is one conflict-free row
 // segment; the next tile is prefetched into registers while the current one is multiplied
 // (double-buffered LDS, one barrier per step).  Split-K partial tiles are summed in a fixed
@@ -21,12 +27,12 @@ namespace bns {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 128, BK = 16;
-constexpr int kGemmThreads = 256;
+constexpr int gemm_threads(int bn, bool a_kcontig) { return (bn == 128 && a_kcontig) ? 512 : 256; }
 
 // Tile of an operand stored [rows][K] (k-contiguous): ROWS rows x 16 k, one float4 per thread and pass.
-template <int ROWS> struct FragK { float4 v[ROWS / 64]; };
+template <int ROWS, int NT> struct FragK { float4 v[ROWS * 4 / NT]; };
 // Tile of an operand stored [K][cols] (contiguous along the tile's COLS columns).
-template <int COLS> struct FragN { float4 v[COLS / 64]; };
+template <int COLS, int NT> struct FragN { float4 v[BK * COLS / 4 / NT]; };
 
 __device__ __forceinline__ float4 load4_guarded(const float *p, bool vec_ok, int valid) {
   // valid = number of leading elements (0..4) that are in range
@@ -42,32 +48,34 @@ __device__ __forceinline__ float4 load4_guarded(const float *p, bool vec_ok, int
 __device__ __forceinline__ int clamp04(int x) { return x < 0 ? 0 : (x > 4 ? 4 : x); }
 
 // rows row0.. of an operand [R][ld] (k-contiguous); k range [k0, k0+16) limited by k_end
-template <int ROWS>
-__device__ __forceinline__ void load_kcontig(FragK<ROWS> &f, const float *__restrict__ base, int ld,
+template <int ROWS, int NT>
+__device__ __forceinline__ void load_kcontig(FragK<ROWS, NT> &f, const float *__restrict__ base, int ld,
                                              int row0, int n_rows, int k0, int k_end, bool vec_ok) {
+  constexpr int PASSES = ROWS * 4 / NT, RPP = NT / 4;  // rows per pass
   const int t = threadIdx.x;
   const int kq = (t & 3) * 4;
   if (vec_ok && row0 + ROWS <= n_rows && k0 + BK <= k_end) {  // whole tile in range (uniform over the block)
 #pragma unroll
-    for (int p = 0; p < ROWS / 64; ++p)
-      f.v[p] = *reinterpret_cast<const float4 *>(base + (size_t)(row0 + (t >> 2) + p * 64) * ld + k0 + kq);
+    for (int p = 0; p < PASSES; ++p)
+      f.v[p] = *reinterpret_cast<const float4 *>(base + (size_t)(row0 + (t >> 2) + p * RPP) * ld + k0 + kq);
     return;
   }
 #pragma unroll
-  for (int p = 0; p < ROWS / 64; ++p) {
-    const int r = row0 + (t >> 2) + p * 64;
+  for (int p = 0; p < PASSES; ++p) {
+    const int r = row0 + (t >> 2) + p * RPP;
     const int valid = r < n_rows ? clamp04(k_end - (k0 + kq)) : 0;
     f.v[p] = load4_guarded(base + (size_t)r * ld + k0 + kq, vec_ok, valid);
   }
 }
-template <int ROWS>
-__device__ __forceinline__ void store_kcontig(const FragK<ROWS> &f, float *__restrict__ tile) {
+template <int ROWS, int NT>
+__device__ __forceinline__ void store_kcontig(const FragK<ROWS, NT> &f, float *__restrict__ tile) {
   constexpr int LD = ROWS + 4;
+  constexpr int PASSES = ROWS * 4 / NT, RPP = NT / 4;
   const int t = threadIdx.x;
   const int kq = (t & 3) * 4;
 #pragma unroll
-  for (int p = 0; p < ROWS / 64; ++p) {
-    const int r = (t >> 2) + p * 64;
+  for (int p = 0; p < PASSES; ++p) {
+    const int r = (t >> 2) + p * RPP;
     tile[(kq + 0) * LD + r] = f.v[p].x;
     tile[(kq + 1) * LD + r] = f.v[p].y;
     tile[(kq + 2) * LD + r] = f.v[p].z;
@@ -76,11 +84,11 @@ __device__ __forceinline__ void store_kcontig(const FragK<ROWS> &f, float *__res
 }
 
 // operand [K][ld] with the tile's COLS columns starting at col0
-template <int COLS>
-__device__ __forceinline__ void load_ncontig(FragN<COLS> &f, const float *__restrict__ base, int ld,
+template <int COLS, int NT>
+__device__ __forceinline__ void load_ncontig(FragN<COLS, NT> &f, const float *__restrict__ base, int ld,
                                              int col0, int n_cols, int k0, int k_end, bool vec_ok) {
   constexpr int TPR = COLS / 4;              // threads per k-row
-  constexpr int KPP = kGemmThreads / TPR;    // k-rows per pass
+  constexpr int KPP = NT / TPR;              // k-rows per pass
   const int t = threadIdx.x;
   const int cq = (t % TPR) * 4;
   if (vec_ok && col0 + COLS <= n_cols && k0 + BK <= k_end) {  // whole tile in range (uniform over the block)
@@ -99,23 +107,24 @@ __device__ __forceinline__ void load_ncontig(FragN<COLS> &f, const float *__rest
 // The same tile moved from global memory straight into LDS (global_load_lds, 16 bytes per lane, a
 // wavefront instruction fills 1 KB = 256 / COLS consecutive tile rows): no registers, no LDS store
 // instructions.  Only for tiles that lie wholly inside the operand; completion is counted by vmcnt.
-template <int COLS>
+template <int COLS, int NT>
 __device__ __forceinline__ void direct_ncontig(const float *__restrict__ base, int ld, int col0, int k0,
                                                float *__restrict__ tile) {
   constexpr int TPR = COLS / 4;    // lanes per tile row
   constexpr int RPI = kWave / TPR; // tile rows per wavefront instruction
+  constexpr int PER_WAVE = (BK * COLS / 256) / (NT / kWave);  // 1 KB instructions per wavefront
   const int lane = lane_id(), wid = threadIdx.x >> 6;
 #pragma unroll
-  for (int p = 0; p < COLS / 64; ++p) {
-    const int inst = wid + p * (kGemmThreads / kWave);
+  for (int p = 0; p < PER_WAVE; ++p) {
+    const int inst = wid + p * (NT / kWave);
     const int k = inst * RPI + lane / TPR, c = (lane % TPR) * 4;
     __builtin_amdgcn_global_load_lds(base + (size_t)(k0 + k) * ld + col0 + c, tile + inst * 256, 16, 0, 0);
   }
 }
-template <int COLS, int LD>
-__device__ __forceinline__ void store_ncontig(const FragN<COLS> &f, float *__restrict__ tile) {
+template <int COLS, int LD, int NT>
+__device__ __forceinline__ void store_ncontig(const FragN<COLS, NT> &f, float *__restrict__ tile) {
   constexpr int TPR = COLS / 4;
-  constexpr int KPP = kGemmThreads / TPR;
+  constexpr int KPP = NT / TPR;
   const int t = threadIdx.x;
   const int cq = (t % TPR) * 4;
 #pragma unroll
@@ -136,19 +145,20 @@ __device__ __forceinline__ void store_ncontig(const FragN<COLS> &f, float *__res
 // product it is the concatenation along M (a_split a multiple of 128).  C2 (nullable): the result is the pair
 // [C | C2] split at column c_split (a multiple of the column tile), both with row stride ldc.
 template <int BN, bool A_KCONTIG, bool B_KCONTIG, int EPI>
-__global__ void __launch_bounds__(kGemmThreads, 4)
+__global__ void __launch_bounds__(gemm_threads(BN, A_KCONTIG), 4)
 gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const float *__restrict__ B,
             int ldb, float *__restrict__ C, int ldc, int k_chunk, bool vec_a, bool vec_b,
             const float *__restrict__ mask_src, float alpha, const int *__restrict__ m_dev,
             const int *__restrict__ k_dev, const Dropout drop, const float *__restrict__ A2, int a_split,
             float *__restrict__ C2, int c_split) {
-  // The W tile of the forward product (k-contiguous A, n-contiguous B) is filled straight from
-  // global memory and is therefore dense; all other staged tiles have padded rows.  (Filling both
-  // tiles of the transposed product directly was measured 25 % slower than staging them through
-  // registers.)
-  constexpr bool kDirectB = A_KCONTIG && !B_KCONTIG;
+  // Every tile is staged through registers.  (Filling the W tile of the forward product straight
+  // into LDS with global_load_lds paid with four wavefronts per block, costs 3 % with eight; doing
+  // it for both tiles of the transposed product was 25 % slower.)
+  constexpr bool kDirectB = false;
   constexpr int LDA = BM + 4, LDB = kDirectB ? BN : BN + 4;
-  constexpr int TI = BN == 128 ? 2 : 1;      // 32-row MFMA tiles per wavefront
+  constexpr int NT = gemm_threads(BN, A_KCONTIG);
+  constexpr bool kEight = NT == 512;
+  constexpr int TI = BN == 128 ? 2 : 1, TJ = kEight ? 1 : 2;  // 32 x 32 MFMA tiles per wavefront: TI x TJ
   const int m_full = M;
   if (m_dev) M = min(M, *m_dev);
   if (k_dev) K = min(K, *k_dev);  // the depth lives on the device (kept boundary rows)
@@ -164,20 +174,20 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
   C += (size_t)blockIdx.y * m_full * ldc;  // split-K: one partial matrix per split
 
   const int lane = lane_id(), wid = threadIdx.x >> 6;
-  const int wm = BN == 128 ? (wid >> 1) * 64 : wid * 32;
-  const int wn = BN == 128 ? (wid & 1) * 64 : 0;
+  const int wm = kEight ? (wid >> 2) * 64 : BN == 128 ? (wid >> 1) * 64 : wid * 32;
+  const int wn = kEight ? (wid & 3) * 32 : BN == 128 ? (wid & 1) * 64 : 0;
   const int l32 = lane & 31, lhi = lane >> 5;
 
-  floatx16 acc[TI][2];
+  floatx16 acc[TI][TJ];
 #pragma unroll
   for (int i = 0; i < TI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  using FA = typename std::conditional<A_KCONTIG, FragK<BM>, FragN<BM>>::type;
-  using FB = typename std::conditional<B_KCONTIG, FragK<BN>, FragN<BN>>::type;
+  using FA = typename std::conditional<A_KCONTIG, FragK<BM, NT>, FragN<BM, NT>>::type;
+  using FB = typename std::conditional<B_KCONTIG, FragK<BN, NT>, FragN<BN, NT>>::type;
   FA fa;
   FB fb;
   bool reg_b = true;  // whether the B tile in flight sits in registers (else it goes straight to LDS)
@@ -190,27 +200,27 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
         if (k0 >= a_split) { Ab = A2; k0a = k0 - a_split; kea = k_end - a_split; }
         else kea = min(k_end, a_split);
       }
-      load_kcontig<BM>(fa, Ab, lda, bm0, M, k0a, kea, vec_a);
+      load_kcontig<BM, NT>(fa, Ab, lda, bm0, M, k0a, kea, vec_a);
     } else {
       // [A | A2] along the columns of the m-contiguous operand: a row tile lies in one of them
       const float *Ab = (A2 && bm0 >= a_split) ? A2 : A;
       const int c0 = (A2 && bm0 >= a_split) ? bm0 - a_split : bm0;
       const int nc = A2 ? a_split : M;
-      load_ncontig<BM>(fa, Ab, lda, c0, nc, k0, k_end, vec_a);
+      load_ncontig<BM, NT>(fa, Ab, lda, c0, nc, k0, k_end, vec_a);
     }
     if constexpr (B_KCONTIG) {
-      load_kcontig<BN>(fb, B, ldb, bn0, N, k0, k_end, vec_b);
+      load_kcontig<BN, NT>(fb, B, ldb, bn0, N, k0, k_end, vec_b);
     } else {
       reg_b = !(kDirectB && vec_b && full_k && bn0 + BN <= N);
-      if (reg_b) load_ncontig<BN>(fb, B, ldb, bn0, N, k0, k_end, vec_b);
-      else direct_ncontig<BN>(B, ldb, bn0, k0, Bs[buf]);
+      if (reg_b) load_ncontig<BN, NT>(fb, B, ldb, bn0, N, k0, k_end, vec_b);
+      else direct_ncontig<BN, NT>(B, ldb, bn0, k0, Bs[buf]);
     }
   };
   auto store_tiles = [&](int buf) {
-    if constexpr (A_KCONTIG) store_kcontig<BM>(fa, As[buf]);
-    else store_ncontig<BM, LDA>(fa, As[buf]);
-    if constexpr (B_KCONTIG) store_kcontig<BN>(fb, Bs[buf]);
-    else if (reg_b) store_ncontig<BN, LDB>(fb, Bs[buf]);
+    if constexpr (A_KCONTIG) store_kcontig<BM, NT>(fa, As[buf]);
+    else store_ncontig<BM, LDA, NT>(fa, As[buf]);
+    if constexpr (B_KCONTIG) store_kcontig<BN, NT>(fb, Bs[buf]);
+    else if (reg_b) store_ncontig<BN, LDB, NT>(fb, Bs[buf]);
     if (!reg_b) __builtin_amdgcn_s_waitcnt(0);  // the direct fill has landed
   };
 
@@ -227,15 +237,15 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
     const float *bs = Bs[buf] + wn + l32;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
-      float a[TI];
+      float a[TI], b[TJ];
 #pragma unroll
       for (int i = 0; i < TI; ++i) a[i] = as[(kk + lhi) * LDA + i * 32];
-      const float b0 = bs[(kk + lhi) * LDB], b1 = bs[(kk + lhi) * LDB + 32];
 #pragma unroll
-      for (int i = 0; i < TI; ++i) {
-        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b0, acc[i][0], 0, 0, 0);
-        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b1, acc[i][1], 0, 0, 0);
-      }
+      for (int j = 0; j < TJ; ++j) b[j] = bs[(kk + lhi) * LDB + j * 32];
+#pragma unroll
+      for (int i = 0; i < TI; ++i)
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < nk) store_tiles(buf ^ 1);
     __syncthreads();
@@ -245,7 +255,7 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
 #pragma unroll
   for (int i = 0; i < TI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < TJ; ++j) {
       int col = bn0 + wn + j * 32 + l32;
       // a result with padded rows (ldc > N, plain store only): columns N..ldc-1 are cleared
       const bool pad_col = col >= N;
@@ -293,8 +303,8 @@ static inline unsigned n_tiles(int M, int N, int bn) {
 
 #define BNS_GEMM_LAUNCH(AK, BK_, EPI, grid, ...)                                                 \
   do {                                                                                           \
-    if (bn == 64) gemm_kernel<64, AK, BK_, EPI><<<grid, kGemmThreads, 0, s>>>(__VA_ARGS__);      \
-    else gemm_kernel<128, AK, BK_, EPI><<<grid, kGemmThreads, 0, s>>>(__VA_ARGS__);              \
+    if (bn == 64) gemm_kernel<64, AK, BK_, EPI><<<grid, gemm_threads(64, AK), 0, s>>>(__VA_ARGS__);  \
+    else gemm_kernel<128, AK, BK_, EPI><<<grid, gemm_threads(128, AK), 0, s>>>(__VA_ARGS__);         \
   } while (0)
 
 hipError_t gemm_nn(int32_t M, int32_t N, int32_t K, const float *A, const float *B, float *C,
