@@ -44,7 +44,8 @@ def kernel_source_hash():
     return h.hexdigest()[:16]
 
 
-def run_workload(cfg, p, kind, steps, warmup, dropout=0.0, extras=False, cpu_baseline=True, calibrate=False):
+def run_workload(cfg, p, kind, steps, warmup, dropout=0.0, extras=False, cpu_baseline=True, calibrate=False,
+                 local_order="native"):
     """Times one workload; -> dict.  extras: also the graph-replay and the cached-input variants,
     the whole-step roofline and the memory figures (the headline workload)."""
     import torch
@@ -53,7 +54,7 @@ def run_workload(cfg, p, kind, steps, warmup, dropout=0.0, extras=False, cpu_bas
     from bns_inputs.workloads import sage_weights
 
     t0 = time.time()
-    w = make_workload(cfg)
+    w = make_workload(cfg, local_order=local_order)
     if kind == 1:
         w.W = sage_weights(220310983 + w.cfg + 300, w.dims)
     P, L = w.part, w.n_layers
@@ -301,6 +302,9 @@ def main():
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="dropout rate on the hidden activations (the five workloads name none: default 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--local-order", choices=["native", "degree"], default="native",
+                    help="numbering of the partition's inner nodes: the generator's (default, what every reported figure "
+                         "uses) or descending degree (the measurement of what node order does to the aggregates)")
     ap.add_argument("--only", action="store_true", help="the headline workload only (no `workloads` sweep, no "
                     "graph-replay / cached variants): what the rocprofv3 summaries under profiles/ run")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -313,7 +317,8 @@ def main():
 
     kind = 1 if args.model == "sage" else 0
     head = run_workload(args.workload, args.p, kind, args.steps, args.warmup, dropout=args.dropout,
-                        extras=not args.only, cpu_baseline=not args.no_cpu_baseline, calibrate=args.calibrate_copy)
+                        extras=not args.only, cpu_baseline=not args.no_cpu_baseline, calibrate=args.calibrate_copy,
+                        local_order=args.local_order)
     others = []
     if not args.only:
         for cfg, p in SWEEP:

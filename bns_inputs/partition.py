@@ -139,3 +139,26 @@ def partition_of_global_graph(part_id: int, g_ptr: np.ndarray, g_col: np.ndarray
                                   src[is_in], dst[is_in] - lo,
                                   src[~is_in], dst[~is_in],
                                   halo_full_degree=full_degree)
+
+
+def relabel_inner(part: Partition, order: np.ndarray) -> Partition:
+    """The same partition with its inner nodes renumbered: new local id i is old local id
+    ``order[i]`` (a permutation of 0..n_in-1).  Local ids are the partitioner's free choice; the
+    boundary nodes keep their order (ascending global id).  Index bookkeeping only."""
+    order = np.asarray(order, dtype=np.int64)
+    rank = np.empty(part.n_in, dtype=np.int64)
+    rank[order] = np.arange(part.n_in, dtype=np.int64)
+    rows = np.repeat(np.arange(part.n_in, dtype=np.int64), np.diff(part.row_ptr0))
+    cols = part.col0.astype(np.int64)
+    inner = cols < part.n_in
+    deg_h = part.deg_halo.astype(np.int64) - 1
+    gid = part.halo_gid
+
+    def full_degree(gids, incidence):
+        return deg_h[np.searchsorted(gid, gids)]
+
+    out = partition_from_entries(part.part_id, part.n_in, rank[rows[inner]], rank[cols[inner]],
+                                 rank[rows[~inner]], gid[cols[~inner] - part.n_in],
+                                 halo_full_degree=full_degree)
+    assert np.array_equal(out.halo_gid, part.halo_gid) and np.array_equal(out.deg_in, part.deg_in[order])
+    return out

@@ -13,7 +13,7 @@ from typing import List
 import numpy as np
 
 from .graphs import chung_lu_partition0, sbm_graph
-from .partition import Partition, partition_of_global_graph
+from .partition import Partition, partition_of_global_graph, relabel_inner
 
 SAMPLING_SEED = 2203
 _BASE_SEED = 220310983
@@ -92,7 +92,11 @@ def tiny_global(cfg_seed: int = _BASE_SEED + 1):
     return ptr, col, X_all, y_all
 
 
-def make_workload(cfg: int, scale: int = 1, part_id: int = 0) -> Workload:
+def make_workload(cfg: int, scale: int = 1, part_id: int = 0, local_order: str = "native") -> Workload:
+    """local_order: how the partition numbers its inner nodes.  "native": the generator's order (no
+    structure: neighbours are spread over the whole id range); "degree": descending full-graph
+    degree (ties by native id), an order a partitioner can emit for free and the measurement of what
+    node order does to the aggregate's cache behaviour."""
     c = CONFIGS[cfg]
     seed = _BASE_SEED + cfg
     dims = list(c["dims"])
@@ -116,6 +120,13 @@ def make_workload(cfg: int, scale: int = 1, part_id: int = 0) -> Workload:
         X = _normal_f32(rng, (part.n_in, dims[0]))
         halo0 = _normal_f32(rng, (part.n_halo, dims[0]))
         labels = make_labels(seed + 200, part.n_in, dims[-1], c["loss"], c["label_zipf"])
+    if local_order == "degree":
+        order = np.argsort(-part.deg_in.astype(np.int64), kind="stable")
+        part = relabel_inner(part, order)
+        X = np.ascontiguousarray(X[order])
+        labels = np.ascontiguousarray(labels[order])
+    elif local_order != "native":
+        raise ValueError("local_order must be 'native' or 'degree'")
     halo_h = [halo0]
     for l in range(1, L):
         rng = np.random.Generator(np.random.PCG64(seed + 400 + l))
@@ -123,7 +134,8 @@ def make_workload(cfg: int, scale: int = 1, part_id: int = 0) -> Workload:
         np.maximum(h, 0.0, out=h)           # post-activation-like
         halo_h.append(h)
     W = glorot_weights(seed + 300, dims)
-    return Workload(cfg=cfg, name=c["name"] + ("" if scale == 1 else f"/scale{scale}"),
+    return Workload(cfg=cfg, name=c["name"] + ("" if scale == 1 else f"/scale{scale}")
+                    + ("" if local_order == "native" else f"/{local_order}-order"),
                     part=part, dims=dims, loss_kind=c["loss"], X=X, halo_h=halo_h,
                     labels=labels, W=W, p_list=list(c["p_list"]))
 

@@ -295,3 +295,20 @@ def test_unbiased_and_variance_closed_form(tiny):
     assert abs(frob.mean() - exact) < 5 * frob.std() / np.sqrt(T)
     assert abs(frob.mean() / exact - 1) < 0.1
     assert exact <= bound
+
+
+def test_renumbering_the_inner_nodes_changes_nothing():
+    """Local ids are the partitioner's free choice: with the inner nodes renumbered by descending
+    degree the same boundary nodes are kept (the draw depends on global ids only), the loss is the
+    same and so are the weight gradients (sums over nodes)."""
+    a = make_workload(3, scale=32)
+    b = make_workload(3, scale=32, local_order="degree")
+    assert np.all(np.diff(b.part.deg_in) <= 0) and not np.all(np.diff(a.part.deg_in) <= 0)
+    ra = orc.step(a.part, a.loss_kind, a.X, a.halo_h, a.labels, a.W, SAMPLING_SEED, 0, 0.5)
+    rb = orc.step(b.part, b.loss_kind, b.X, b.halo_h, b.labels, b.W, SAMPLING_SEED, 0, 0.5)
+    assert np.array_equal(ra["sub"]["kept_ids"], rb["sub"]["kept_ids"])
+    np.testing.assert_allclose(rb["loss"], ra["loss"], rtol=1e-12)
+    for x, y in zip(ra["dW"], rb["dW"]):
+        np.testing.assert_allclose(y, x, rtol=1e-9, atol=1e-11)
+    for x, y in zip(ra["dhalo"][1:], rb["dhalo"][1:]):
+        np.testing.assert_allclose(y, x, rtol=1e-9, atol=1e-11)
