@@ -209,8 +209,11 @@ bns_status bns_graph_replay(bns_ctx *ctx, int32_t n_epochs, void *stream);
  * parentheses); they differ in kernel boundaries, in what BNS_VIEW_A holds and in what the phase
  * timers attribute to BNS_PHASE_SPMM_FWD / BNS_PHASE_GEMM_FWD.
  *   BNS_LAYER_TWO_KERNELS  aggregate (Eq. 1), then update (Eq. 2); BNS_VIEW_A = the aggregate.
- *   BNS_LAYER_ONE_KERNEL   the same two steps in one kernel (GCN layer, input width a multiple of
- *                          4 between 68 and 128); BNS_VIEW_A = the aggregate.
+ *   BNS_LAYER_ONE_KERNEL   the same two steps in one kernel: input width a multiple of 4 between 68
+ *                          and 128; the mean-aggregator layer, whose update is twice as deep, only
+ *                          with an output width of at most 256 and at most 3.25 times the average
+ *                          number of entries per row (a longer update is faster as a kernel of its
+ *                          own); BNS_VIEW_A = the aggregate.
  *   BNS_LAYER_UPDATE_FIRST a GCN layer whose output is at most 3/4 as wide as its input (and whose
  *                          aggregate thereby gathers at least 2^24 fewer floats) is run as
  *                          P (H W): the products H W and H_U W first, then the aggregate at the

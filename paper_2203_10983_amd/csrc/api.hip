@@ -38,9 +38,9 @@ struct Layout {
   float *dis_in, *dis_halo;
   StaticSplit split;
   // scratch shared by all calls
-  int32_t *tile_sums;
+  int32_t *tile_sums, *kept_counts;
   uint64_t *ballots;
-  int32_t *kpos, *hlen;
+  int32_t *kpos;
   float *Hu, *Hu2, *G0, *G1, *G2, *partials, *loss_partials;  // Hu2: boundary rows at the output width
   int2 *halo_rec;  // per kept boundary node: (boundary index, weight) for the aggregates that read the rows in place
   float *inv_deg;            // 1 / (full-graph degree) of the inner nodes, for the mean aggregator
@@ -105,6 +105,18 @@ int gather_stride(int d_in, int d_out) {
   return (d_out % 4 != 0 && ld < 128 && ld <= d_in) ? ld : d_out;
 }
 
+// Aggregate and update of a layer in one kernel?  The kernel's two phases (gather, product) do not
+// overlap, so it pays only while the product is short beside the gather: measured on the five
+// workloads, up to about 6.5 multiply-adds of the update per gathered feature element (GCN layers of
+// workload 5: 4.4 and 6.0, faster in one kernel; mean-aggregator layers, whose update is twice as
+// deep: workload 3 at 5.1 faster, workload 5 at 8.9 and 11.9 slower).
+bool one_kernel_layer(const bns_partition_desc &part, int layer_kind, int d_in, int d_out) {
+  if (layer_kind == 0) return spmm_gemm_fwd_supported(d_in);  // every GCN shape measured so far gains
+  if (!spmm_gemm_fwd_concat_supported(d_in, d_out)) return false;
+  const double avg_len = (double)part.nnz0 / (double)part.n_in;
+  return 2.0 * d_out <= 6.5 * avg_len;
+}
+
 bool valid_desc(const bns_partition_desc *p, const bns_model_desc *m) {
   if (!p || !m || !m->dims) return false;
   if (p->n_in < 1 || p->n_halo < 0 || p->nnz0 < p->n_in || p->e_in < p->n_in || p->e_bd < 0) return false;
@@ -150,13 +162,13 @@ size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, La
   w.split.inner_ptr = c.take<int32_t>(n_in + 1);
   w.split.bd_ptr = c.take<int32_t>(n_in + 1);
   w.split.in_col = c.take<int32_t>(p->e_in);
-  w.split.in_row = c.take<int32_t>(p->e_in);
+  w.split.in_bdp = c.take<int32_t>(p->e_in);
   w.split.bd_b = c.take<int32_t>(p->e_bd);
   w.split.bd_row = c.take<int32_t>(p->e_bd);
   w.tile_sums = c.take<int32_t>(scan_tiles(p->nnz0 + n_in + B) + 4);
+  w.kept_counts = c.take<int32_t>(kept_counts_size(B));
   w.ballots = c.take<uint64_t>((B + 63) / 64 + 1);
   w.kpos = c.take<int32_t>(p->e_bd + 1);
-  w.hlen = c.take<int32_t>(B + 1);
   w.Hu = c.take<float>(B * d_in_max);
   w.Hu2 = c.take<float>(B * d_first_max);
   w.halo_rec = c.take<int2>(B + 1);
@@ -265,7 +277,7 @@ int layer_plan(const bns_ctx *ctx, int layer, const float *X) {
   // worth its extra launches only when the aggregate is big: at least 2^24 fewer floats gathered
   const bool big = (int64_t)ctx->part.nnz0 * (d_in - d_out) >= ((int64_t)1 << 24);
   if (!cached && big && update_first_shape(ctx->layer_kind, d_in, d_out)) return BNS_LAYER_UPDATE_FIRST;
-  if (ctx->layer_kind == 0 && spmm_gemm_fwd_supported(d_in)) return BNS_LAYER_ONE_KERNEL;
+  if (one_kernel_layer(ctx->part, ctx->layer_kind, d_in, d_out)) return BNS_LAYER_ONE_KERNEL;
   return BNS_LAYER_TWO_KERNELS;
 }
 
@@ -317,7 +329,7 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
   }
   const float *w_col = sage ? nullptr : ctx->ws.dis_in;
   const float *row_scale = sage ? ctx->ws.inv_deg : ctx->ws.dis_in;
-  if (!sage && spmm_gemm_fwd_supported(d_in)) {
+  if (one_kernel_layer(ctx->part, ctx->layer_kind, d_in, d_out)) {
     // aggregate and update in one kernel; the rows cut into several segments are finished first
     {
       PhaseTimer t(ctx, BNS_PHASE_SPMM_LONG, s);
@@ -328,7 +340,7 @@ bns_status layer_fwd_impl(bns_ctx *ctx, int layer, double p, const float *H_in, 
     PhaseTimer t(ctx, BNS_PHASE_SPMM_FWD, s);
     BNS_TRY("spmm_gemm_fwd", spmm_gemm_fwd(ctx->ws.plan_f, n_in, d_in, d_out, ctx->cur_row_ptr, ctx->cur_col_idx,
                                            w_col, row_scale, H_in, halo_h, ctx->ws.spmm_partials, A_saved,
-                                           part, W, H_out, relu, dropout_of(ctx, layer, relu), s));
+                                           part, W, H_out, relu, dropout_of(ctx, layer, relu), s, sage));
     return BNS_OK;
   }
   {
@@ -500,7 +512,7 @@ bns_status build_impl(bns_ctx *ctx, int32_t *row_ptr, int32_t *col_idx, int32_t 
                             ctx->ws.tile_sums, row_ptr, col_idx, nnz, s));
   BNS_TRY("build_transposed_csr",
           build_transposed_csr(P.n_in, P.n_halo, P.e_in, P.t_in_ptr, P.t_in_col, P.halo_ptr, P.halo_col,
-                               ctx->cur_kept, ctx->cur_n_kept, ctx->ws.hlen, ctx->ws.tile_sums,
+                               ctx->cur_kept, ctx->cur_n_kept, ctx->ws.kept_counts,
                                t_row_ptr, t_col_idx,
                                // the workspace arrays hold the static rows since bns_create
                                !(t_row_ptr == ctx->ws.t_row_ptr && t_col_idx == ctx->ws.t_col_idx), true, s));
@@ -555,7 +567,7 @@ bns_status bns_create(bns_ctx **out, const bns_partition_desc *part, const bns_m
   // the rows of the inner nodes in the workspace's transposed CSR are the same in every epoch
   BNS_TRY("build_transposed_csr(static rows)",
           build_transposed_csr(part->n_in, part->n_halo, part->e_in, part->t_in_ptr, part->t_in_col, part->halo_ptr,
-                               part->halo_col, nullptr, nullptr, ctx->ws.hlen, ctx->ws.tile_sums, ctx->ws.t_row_ptr,
+                               part->halo_col, nullptr, nullptr, ctx->ws.kept_counts, ctx->ws.t_row_ptr,
                                ctx->ws.t_col_idx, true, false, s));
   BNS_TRY("set-up sync", hipStreamSynchronize(s));
   return BNS_OK;

@@ -10,8 +10,10 @@
 //
 //   kpos[k]     = kept boundary entries before boundary entry k            (prefix sum)
 //   row_ptr[v]  = inner_ptr[v] + kpos[bd_ptr[v]]
-//   inner entry j of row v      -> col_idx[j + row_ptr[v] - inner_ptr[v]]
+//   inner entry j of row v      -> col_idx[j + kpos[bd_ptr[v]]]
 //   kept boundary entry k, row v -> col_idx[inner_ptr[v+1] + kpos[k]]
+#include <algorithm>
+
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -39,7 +41,7 @@ __global__ void __launch_bounds__(kThreads)
 split_entries_kernel(int32_t n_in, const int32_t *__restrict__ row_ptr0,
                      const int32_t *__restrict__ col0, const int32_t *__restrict__ inner_ptr,
                      int32_t *__restrict__ bd_ptr, int32_t *__restrict__ in_col,
-                     int32_t *__restrict__ in_row, int32_t *__restrict__ bd_b,
+                     int32_t *__restrict__ in_bdp, int32_t *__restrict__ bd_b,
                      int32_t *__restrict__ bd_row) {
   const int lane = lane_id();
   const int waves = gridDim.x * (kThreads / kWave);
@@ -55,7 +57,7 @@ split_entries_kernel(int32_t n_in, const int32_t *__restrict__ row_ptr0,
     for (int e = e0 + lane; e < e1; e += kWave) {
       const int c = col0[e];
       const int o = e - e0;
-      if (o < ni) { in_col[i0 + o] = c; in_row[i0 + o] = v; }
+      if (o < ni) { in_col[i0 + o] = c; in_bdp[i0 + o] = b0; }
       else { bd_b[b0 + o - ni] = c - n_in; bd_row[b0 + o - ni] = v; }
     }
   }
@@ -91,7 +93,7 @@ hipError_t build_static_split(int32_t n_in, const int32_t *row_ptr0, const int32
   if (e != hipSuccess) return e;
   const int blocks = (n_in + 1 + (kThreads / kWave) - 1) / (kThreads / kWave);
   split_entries_kernel<<<blocks < 65536 ? blocks : 65536, kThreads, 0, s>>>(
-      n_in, row_ptr0, col0, sp.inner_ptr, sp.bd_ptr, sp.in_col, sp.in_row, sp.bd_b, sp.bd_row);
+      n_in, row_ptr0, col0, sp.inner_ptr, sp.bd_ptr, sp.in_col, sp.in_bdp, sp.bd_b, sp.bd_row);
   return hipGetLastError();
 }
 
@@ -135,10 +137,12 @@ bd_keep_tile_sums_kernel(int64_t e_bd, const int32_t *__restrict__ bd_b,
 __global__ void __launch_bounds__(kThreads)
 bd_fill_kernel(int32_t n_in, int64_t e_bd, const int32_t *__restrict__ bd_b,
                const int32_t *__restrict__ bd_row, const uint64_t *__restrict__ ballots,
-               const int32_t *__restrict__ remap, const int32_t *__restrict__ tile_offsets, const int32_t *__restrict__ inner_ptr,
+               const int32_t *__restrict__ remap, const int32_t *__restrict__ tile_counts, const int32_t *__restrict__ inner_ptr,
                int32_t *__restrict__ kpos, int32_t *__restrict__ col_idx) {
   __shared__ int wave_cnt[kWavesPerBlock];
   const int lane = lane_id(), wid = threadIdx.x / kWave;
+  // kept boundary entries in the tiles before this one: summed here from the raw per-tile counts
+  const int tile_offset = tiles_before<kThreads>(tile_counts, blockIdx.x, gridDim.x, nullptr);
   const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)wid * (kPasses * kWave);
   int b[kPasses];
   unsigned long long mask[kPasses];
@@ -152,7 +156,7 @@ bd_fill_kernel(int32_t n_in, int64_t e_bd, const int32_t *__restrict__ bd_b,
   }
   if (lane == 0) wave_cnt[wid] = cnt;
   __syncthreads();
-  int run = tile_offsets[blockIdx.x];  // kept boundary entries before this wavefront's piece
+  int run = tile_offset;  // kept boundary entries before this wavefront's piece
   for (int w = 0; w < wid; ++w) run += wave_cnt[w];
   const unsigned long long lower = (1ull << lane) - 1ull;
 #pragma unroll
@@ -169,26 +173,22 @@ bd_fill_kernel(int32_t n_in, int64_t e_bd, const int32_t *__restrict__ bd_b,
   }
 }
 
+// Row starts and the inner entries in one launch: both follow in closed form from kpos (row v's
+// entries move down by the kept boundary entries of the rows before it, kpos[bd_ptr[v]]; every
+// inner entry carries its row's bd_ptr, so it needs one gather).
 __global__ void __launch_bounds__(kThreads)
-row_ptr_kernel(int32_t n_in, int64_t e_bd, const int32_t *__restrict__ inner_ptr,
-               const int32_t *__restrict__ bd_ptr, const int32_t *__restrict__ kpos,
-               int32_t *__restrict__ row_ptr, int32_t *__restrict__ nnz) {
-  const int v = blockIdx.x * kThreads + threadIdx.x;
-  if (v > n_in) return;
-  const int r = inner_ptr[v] + (e_bd > 0 ? kpos[bd_ptr[v]] : 0);
-  row_ptr[v] = r;
-  if (v == n_in) *nnz = r;
-}
-
-__global__ void __launch_bounds__(kThreads)
-inner_fill_kernel(int64_t e_in, const int32_t *__restrict__ in_col,
-                  const int32_t *__restrict__ in_row, const int32_t *__restrict__ row_ptr,
-                  const int32_t *__restrict__ inner_ptr, int32_t *__restrict__ col_idx) {
+finish_csr_kernel(int32_t n_in, int64_t e_in, int64_t e_bd, const int32_t *__restrict__ inner_ptr,
+                  const int32_t *__restrict__ bd_ptr, const int32_t *__restrict__ kpos,
+                  const int32_t *__restrict__ in_col, const int32_t *__restrict__ in_bdp,
+                  int32_t *__restrict__ row_ptr, int32_t *__restrict__ col_idx, int32_t *__restrict__ nnz) {
   const int64_t stride = (int64_t)gridDim.x * kThreads;
-  for (int64_t j = (int64_t)blockIdx.x * kThreads + threadIdx.x; j < e_in; j += stride) {
-    const int v = in_row[j];
-    col_idx[j + (row_ptr[v] - inner_ptr[v])] = in_col[j];
+  const int64_t t0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  for (int64_t v = t0; v <= n_in; v += stride) {
+    const int r = inner_ptr[v] + (e_bd > 0 ? kpos[bd_ptr[v]] : 0);
+    row_ptr[v] = r;
+    if (v == n_in) *nnz = r;
   }
+  for (int64_t j = t0; j < e_in; j += stride) col_idx[j + (e_bd > 0 ? kpos[in_bdp[j]] : 0)] = in_col[j];
 }
 
 hipError_t build_sampled_csr(int32_t n_in, int64_t e_in, int64_t e_bd, const StaticSplit &sp,
@@ -199,28 +199,76 @@ hipError_t build_sampled_csr(int32_t n_in, int64_t e_in, int64_t e_bd, const Sta
     bd_keep_tile_sums_kernel<<<nb, kThreads, 0, s>>>(e_bd, sp.bd_b, ballots, tile_sums);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    e = scan_sums_inplace(tile_sums, nb, nullptr, s);
-    if (e != hipSuccess) return e;
     bd_fill_kernel<<<nb, kThreads, 0, s>>>(n_in, e_bd, sp.bd_b, sp.bd_row, ballots, remap, tile_sums,
                                            sp.inner_ptr, kpos, col_idx);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
   }
-  row_ptr_kernel<<<(n_in + 1 + kThreads - 1) / kThreads, kThreads, 0, s>>>(
-      n_in, e_bd, sp.inner_ptr, sp.bd_ptr, kpos, row_ptr, nnz);
-  int64_t blocks = (e_in + kThreads * 4 - 1) / (kThreads * 4);
+  int64_t blocks = (std::max<int64_t>(e_in, (int64_t)n_in + 1) + kThreads * 4 - 1) / (kThreads * 4);
   if (blocks < 1) blocks = 1;
-  inner_fill_kernel<<<(unsigned)blocks, kThreads, 0, s>>>(e_in, sp.in_col, sp.in_row, row_ptr,
-                                                          sp.inner_ptr, col_idx);
+  finish_csr_kernel<<<(unsigned)blocks, kThreads, 0, s>>>(n_in, e_in, e_bd, sp.inner_ptr, sp.bd_ptr, kpos, sp.in_col,
+                                                          sp.in_bdp, row_ptr, col_idx, nnz);
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------- transpose
+// Rows of the kept boundary nodes in the transposed CSR: kept node r (boundary node b =
+// kept_ids[r]) gets b's static list of inner neighbours.  Pass 1 counts the entries of every tile of
+// kScanTile kept nodes and of each of its kSubTiles pieces; pass 2 runs one block per piece: the row
+// starts follow from the counts of the tiles before (summed by the block itself), of the pieces
+// before in the same tile and a scan inside the piece; pass 3 copies the lists, eight lanes each
+// (a pass of its own: copying inside pass 2 left too few lanes busy and took three times as long).
+constexpr int kRowsPerThread = kScanTile / kThreads;
+constexpr int kSubTiles = kScanTile / kThreads;            // pieces of kThreads rows
+constexpr int kLanesPerPiece = kThreads / kSubTiles;       // threads of pass 1 that cover one piece
+static_assert(kLanesPerPiece == 32, "pass 1 folds the counts of a piece inside half a wavefront");
+
+// counts: int32[nb * (1 + kSubTiles)]: nb tile counts, then kSubTiles piece counts per tile
 __global__ void __launch_bounds__(kThreads)
-kept_len_kernel(const int32_t *__restrict__ n_kept, const int32_t *__restrict__ kept_ids,
-                const int32_t *__restrict__ halo_ptr, int32_t *__restrict__ hlen) {
-  const int r = blockIdx.x * kThreads + threadIdx.x;
-  if (r >= *n_kept) return;
-  const int b = kept_ids[r];
-  hlen[r] = halo_ptr[b + 1] - halo_ptr[b];
+kept_len_counts_kernel(const int32_t *__restrict__ n_kept, const int32_t *__restrict__ kept_ids,
+                       const int32_t *__restrict__ halo_ptr, int32_t *__restrict__ counts) {
+  const int n = *n_kept;
+  const int r0 = blockIdx.x * kScanTile + threadIdx.x * kRowsPerThread;
+  int sum = 0;
+#pragma unroll
+  for (int k = 0; k < kRowsPerThread; ++k)
+    if (r0 + k < n) {
+      const int b = kept_ids[r0 + k];
+      sum += halo_ptr[b + 1] - halo_ptr[b];
+    }
+  int piece = sum;  // the 32 consecutive threads of a piece sit in one half of a wavefront
+#pragma unroll
+  for (int off = kLanesPerPiece / 2; off > 0; off >>= 1) piece += __shfl_xor(piece, off, kWave);
+  if (threadIdx.x % kLanesPerPiece == 0)
+    counts[gridDim.x + blockIdx.x * kSubTiles + threadIdx.x / kLanesPerPiece] = piece;
+  int total;
+  block_exclusive_scan<kThreads>(sum, &total);
+  if (threadIdx.x == 0) counts[blockIdx.x] = total;
+}
+
+__global__ void __launch_bounds__(kThreads)
+kept_row_starts_kernel(const int32_t *__restrict__ n_kept, const int32_t *__restrict__ kept_ids,
+                       const int32_t *__restrict__ halo_ptr, const int32_t *__restrict__ counts, int32_t nb,
+                       int32_t first, int32_t *__restrict__ t_tail_ptr) {
+  const int n = *n_kept;
+  const int tile = blockIdx.x / kSubTiles, sub = blockIdx.x % kSubTiles;
+  const int row0 = tile * kScanTile + sub * kThreads;
+  if (n == 0 && blockIdx.x == 0 && threadIdx.x == 0) t_tail_ptr[0] = first;
+  if (row0 >= n) return;
+  int base = first + tiles_before<kThreads>(counts, tile, nb, nullptr);
+  for (int i = 0; i < sub; ++i) base += counts[nb + tile * kSubTiles + i];
+  const int r = row0 + threadIdx.x;
+  int len = 0;
+  if (r < n) {
+    const int b = kept_ids[r];
+    len = halo_ptr[b + 1] - halo_ptr[b];
+  }
+  int total;
+  const int dst = base + block_exclusive_scan<kThreads>(len, &total);
+  if (r < n) {
+    t_tail_ptr[r] = dst;
+    if (r == n - 1) t_tail_ptr[n] = dst + len;
+  }
 }
 
 // Eight lanes copy one kept boundary node's list of inner rows.
@@ -250,8 +298,8 @@ copy_static_kernel(const int32_t *__restrict__ a_src, int64_t a_n, int32_t *__re
 hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
                                 const int32_t *t_in_ptr, const int32_t *t_in_col,
                                 const int32_t *halo_ptr, const int32_t *halo_col,
-                                const int32_t *kept_ids, const int32_t *n_kept, int32_t *hlen,
-                                int32_t *tile_sums, int32_t *t_row_ptr, int32_t *t_col_idx,
+                                const int32_t *kept_ids, const int32_t *n_kept,
+                                int32_t *kept_counts, int32_t *t_row_ptr, int32_t *t_col_idx,
                                 bool static_rows, bool kept_rows, hipStream_t s) {
   // rows of inner nodes never change: the transpose of the inner-inner block (copied by a kernel,
   // so that the whole step stays a plain chain of kernel nodes under graph capture)
@@ -266,9 +314,13 @@ hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
   if (e != hipSuccess) return e;
   if (n_halo == 0 || !kept_rows) return hipSuccess;
   // rows of kept boundary nodes: their static lists of inner neighbours, in kept order
-  kept_len_kernel<<<(n_halo + kThreads - 1) / kThreads, kThreads, 0, s>>>(n_kept, kept_ids,
-                                                                         halo_ptr, hlen);
-  e = scan_exclusive_i32(hlen, t_row_ptr + n_in, n_halo, n_kept, tile_sums, nullptr, (int32_t)e_in, s);
+  const int nb = scan_tiles(n_halo);
+  kept_len_counts_kernel<<<nb, kThreads, 0, s>>>(n_kept, kept_ids, halo_ptr, kept_counts);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  kept_row_starts_kernel<<<nb * kSubTiles, kThreads, 0, s>>>(n_kept, kept_ids, halo_ptr, kept_counts, nb,
+                                                             (int32_t)e_in, t_row_ptr + n_in);
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int64_t threads = (int64_t)n_halo * 8;
   kept_rows_fill_kernel<<<(unsigned)((threads + kThreads - 1) / kThreads), kThreads, 0, s>>>(

@@ -75,4 +75,36 @@ __device__ __forceinline__ int block_exclusive_scan(int x, int *block_total) {
   return base + inc - x;
 }
 
+// Number of items in the tiles before tile `tile`, from the per-tile counts sums[0..nb): every
+// block adds up the counts of its predecessors itself (a few thousand L2-resident integers), which
+// saves the separate one-block scan kernel between a counting pass and its consumer.  Every thread
+// gets the result; *total (nullable, block-uniform) receives the sum over all nb tiles.
+template <int NT>
+__device__ __forceinline__ int tiles_before(const int32_t *__restrict__ sums, int tile, int nb, int *total) {
+  __shared__ int red[2][NT / kWave];
+  int before = 0, all = 0;
+  const int n = total ? nb : tile;
+  for (int i = threadIdx.x; i < n; i += NT) {
+    const int x = sums[i];
+    all += x;
+    if (i < tile) before += x;
+  }
+  before = wave_sum(before);
+  all = wave_sum(all);
+  if (lane_id() == 0) {
+    red[0][threadIdx.x / kWave] = before;
+    red[1][threadIdx.x / kWave] = all;
+  }
+  __syncthreads();
+  int b = 0, a = 0;
+#pragma unroll
+  for (int w = 0; w < NT / kWave; ++w) {
+    b += red[0][w];
+    a += red[1][w];
+  }
+  __syncthreads();
+  if (total) *total = a;
+  return b;
+}
+
 }  // namespace bns

@@ -1,4 +1,8 @@
-// Aggregate (Eq. 1) and update (Eq. 2) of one GCN layer in one kernel.
+// Aggregate (Eq. 1) and update (Eq. 2) of one layer in one kernel: the GCN layer of Appendix A, or
+// (SAGE) the mean-aggregator layer of Section 2, whose update [z | h] [W_n ; W_s] runs as two
+// products from the same LDS tile: first the aggregated rows z times W_n, then, after the tile has
+// been overwritten with the rows' own features h (one coalesced read), h times W_s into the same
+// accumulators.
 //
 // The aggregate is bound by the rate at which the L2s pull neighbour rows from the fabric and
 // leaves the matrix cores idle; the update of a 128-wide layer needs almost as much time for
@@ -23,14 +27,15 @@ constexpr int kFBk = 16, kFBn = 128, kFLdb = kFBn + 4;
 
 struct FusedArgs {
   SpmmArgs sp;
-  const float *W;   // [d_in, d_out]
-  float *H_out;     // [n_in, d_out]
+  const float *W;       // [d_in, d_out]; SAGE: [2 d_in, d_out], neighbour half first
+  const float *H_self;  // SAGE: the layer's input [n_in, d_in] (the node's own features)
+  float *H_out;         // [n_in, d_out]
   int32_t d_out;
   bool relu, vec_w;
   Dropout drop;
 };
 
-template <int LPR>
+template <int LPR, bool SAGE>
 __global__ void __launch_bounds__(kFThreads, 6) __attribute__((amdgpu_num_sgpr(96))) spmm_gemm_kernel(const FusedArgs f) {
   constexpr int VEC = 4;
   using V = typename Vec<VEC>::T;
@@ -139,11 +144,11 @@ __global__ void __launch_bounds__(kFThreads, 6) __attribute__((amdgpu_num_sgpr(9
   constexpr int nk = k_pad / kFBk;  // 8, an even number of steps
   const int t = threadIdx.x;
   const int bk = t >> 5, bq = (t & 31) * 4;  // this thread's piece of a W tile: row bk, columns bq..bq+3
-  auto load_w = [&](int n0, int k0) -> float4 {
+  auto load_w_from = [&](const float *Wb, int n0, int k0) -> float4 {
     const int k = k0 + bk, c = n0 + bq;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     if (k < d && n0 < N) {
-      const float *p = f.W + (size_t)k * N + c;
+      const float *p = Wb + (size_t)k * N + c;
       if (f.vec_w && c + 3 < N) {
         v = *reinterpret_cast<const float4 *>(p);
       } else {
@@ -155,34 +160,9 @@ __global__ void __launch_bounds__(kFThreads, 6) __attribute__((amdgpu_num_sgpr(9
     }
     return v;
   };
-  float4 wv = load_w(0, 0);  // in flight across the barrier that ends the gather
-  __syncthreads();
-  for (int n0 = 0; n0 < N; n0 += kFBn) {
-    floatx16 acc;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-    *reinterpret_cast<float4 *>(&Bs[0][bk * kFLdb + bq]) = wv;
-    __syncthreads();
-    // a wavefront whose 32 columns all lie past the last one (the tail tile of a width such as
-    // 172) still stages W and keeps the barriers, but issues no products
-    const bool has_cols = n0 + wn < N;
-#pragma unroll 1
-    for (int kt = 0; kt < nk; ++kt) {
-      const int buf = kt & 1;
-      // request the next piece (next depth step, or the first one of the next column tile), issue
-      // this step's products, and only then wait for the piece and stage it
-      wv = kt + 1 < nk ? load_w(n0, (kt + 1) * kFBk) : load_w(n0 + kFBn, 0);
-      const float *as = As + (wm + l32) * kFLda + kt * kFBk + lhi;
-      const float *bs = Bs[buf] + lhi * kFLdb + wn + l32;
-      if (has_cols) {
-#pragma unroll
-        for (int kk = 0; kk < kFBk; kk += 2)
-          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(as[kk], bs[kk * kFLdb], acc, 0, 0, 0);
-      }
-      if (kt + 1 < nk) *reinterpret_cast<float4 *>(&Bs[buf ^ 1][bk * kFLdb + bq]) = wv;
-      __syncthreads();
-    }
-    // C element of (lane, register r): row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32
+  auto load_w = [&](int n0, int k0) -> float4 { return load_w_from(f.W, n0, k0); };
+  // C element of (lane, register r): row = 8*(r/4) + 4*(lane/32) + r%4, column = lane%32
+  auto store_tile = [&](const floatx16 &acc, int n0) {
     const int col = n0 + wn + l32;
     if (col < N) {
 #pragma unroll 1
@@ -208,28 +188,119 @@ __global__ void __launch_bounds__(kFThreads, 6) __attribute__((amdgpu_num_sgpr(9
         }
       }
     }
+  };
+  float4 wv = load_w(0, 0);  // in flight across the barrier that ends the gather
+  __syncthreads();
+  if constexpr (SAGE) {
+    // [z | h] [W_n ; W_s]: both operands pass through the one LDS tile, so the accumulators of every
+    // column tile (at most two: d_out <= 256) stay live across the two products.
+    floatx16 acc2[2];
+#pragma unroll
+    for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc2[tl][i] = 0.f;
+    const int ntile = (N + kFBn - 1) / kFBn;
+#pragma unroll 1
+    for (int op = 0; op < 2; ++op) {
+      const float *Wop = f.W + (size_t)op * d * N;
+      if (op == 1) {
+        // every wavefront is past the barrier that ended the last step of z W_n: the tile is free.
+        // Rows past the last one and the depth padding stay zero.
+        for (int idx = t; idx < kFM * nvec; idx += kFThreads) {
+          const int r = idx / nvec, c4 = idx - r * nvec;
+          V x = V{};
+          if (row0 + r < a.n_split) x = reinterpret_cast<const V *>(f.H_self + (size_t)(row0 + r) * d)[c4];
+          const float *px = reinterpret_cast<const float *>(&x);
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) As[r * kFLda + c4 * VEC + i] = px[i];
+        }
+      }
+#pragma unroll
+      for (int tl = 0; tl < 2; ++tl) {
+        if (tl < ntile) {
+          const int n0 = tl * kFBn;
+          *reinterpret_cast<float4 *>(&Bs[0][bk * kFLdb + bq]) = wv;
+          __syncthreads();  // also publishes the tile of own features written above
+          const bool has_cols = n0 + wn < N;
+#pragma unroll 1
+          for (int kt = 0; kt < nk; ++kt) {
+            const int buf = kt & 1;
+            // the next piece: next depth step, else the first piece of the next column tile, else of W_s
+            if (kt + 1 < nk) wv = load_w_from(Wop, n0, (kt + 1) * kFBk);
+            else if (tl + 1 < ntile) wv = load_w_from(Wop, n0 + kFBn, 0);
+            else if (op == 0) wv = load_w_from(f.W + (size_t)d * N, 0, 0);
+            const float *as = As + (wm + l32) * kFLda + kt * kFBk + lhi;
+            const float *bs = Bs[buf] + lhi * kFLdb + wn + l32;
+            if (has_cols) {
+#pragma unroll
+              for (int kk = 0; kk < kFBk; kk += 2)
+                acc2[tl] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[kk], bs[kk * kFLdb], acc2[tl], 0, 0, 0);
+            }
+            if (kt + 1 < nk) *reinterpret_cast<float4 *>(&Bs[buf ^ 1][bk * kFLdb + bq]) = wv;
+            __syncthreads();
+          }
+        }
+      }
+    }
+    store_tile(acc2[0], 0);
+    if (ntile > 1) store_tile(acc2[1], kFBn);
+    return;
+  }
+  for (int n0 = 0; n0 < N; n0 += kFBn) {
+    floatx16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    *reinterpret_cast<float4 *>(&Bs[0][bk * kFLdb + bq]) = wv;
+    __syncthreads();
+    // a wavefront whose 32 columns all lie past the last one (the tail tile of a width such as
+    // 172) still stages W and keeps the barriers, but issues no products
+    const bool has_cols = n0 + wn < N;
+#pragma unroll 1
+    for (int kt = 0; kt < nk; ++kt) {
+      const int buf = kt & 1;
+      // request the next piece (next depth step, or the first one of the next column tile), issue
+      // this step's products, and only then wait for the piece and stage it
+      wv = kt + 1 < nk ? load_w(n0, (kt + 1) * kFBk) : load_w(n0 + kFBn, 0);
+      const float *as = As + (wm + l32) * kFLda + kt * kFBk + lhi;
+      const float *bs = Bs[buf] + lhi * kFLdb + wn + l32;
+      if (has_cols) {
+#pragma unroll
+        for (int kk = 0; kk < kFBk; kk += 2)
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(as[kk], bs[kk * kFLdb], acc, 0, 0, 0);
+      }
+      if (kt + 1 < nk) *reinterpret_cast<float4 *>(&Bs[buf ^ 1][bk * kFLdb + bq]) = wv;
+      __syncthreads();
+    }
+    store_tile(acc, n0);
   }
 }
 
 bool spmm_gemm_fwd_supported(int32_t d_in) { return d_in % 4 == 0 && d_in > 64 && d_in <= 128; }
 
+bool spmm_gemm_fwd_concat_supported(int32_t d_in, int32_t d_out) {
+  return spmm_gemm_fwd_supported(d_in) && d_out <= 2 * kFBn;
+}
+
 hipError_t spmm_gemm_fwd(const SegPlan &plan, int32_t n_in, int32_t d_in, int32_t d_out, const int32_t *row_ptr,
                          const int32_t *col_idx, const float *w_col, const float *row_scale,
                          const float *H_in, const float *Hu, float *partials, float *A,
                          const SpmmRowPart &part, const float *W, float *H_out, bool relu,
-                         const Dropout &drop, hipStream_t s) {
+                         const Dropout &drop, hipStream_t s, bool concat_self) {
   if (!spmm_gemm_fwd_supported(d_in)) return hipErrorInvalidValue;
+  if (concat_self && !spmm_gemm_fwd_concat_supported(d_in, d_out)) return hipErrorInvalidValue;
   if (n_in <= 0) return hipSuccess;
   FusedArgs f;
   f.sp = spmm_fwd_args(plan, n_in, d_in, row_ptr, col_idx, w_col, row_scale, H_in, Hu, partials, A, part);
   f.W = W;
+  f.H_self = concat_self ? H_in : nullptr;
   f.H_out = H_out;
   f.d_out = d_out;
   f.relu = relu;
   f.vec_w = (d_out % 4 == 0) && (((uintptr_t)W & 15) == 0);
   f.drop = drop;
   const unsigned blocks = (unsigned)((n_in + kFM - 1) / kFM);
-  spmm_gemm_kernel<32><<<blocks, kFThreads, 0, s>>>(f);
+  if (concat_self) spmm_gemm_kernel<32, true><<<blocks, kFThreads, 0, s>>>(f);
+  else spmm_gemm_kernel<32, false><<<blocks, kFThreads, 0, s>>>(f);
   return hipGetLastError();
 }
 

@@ -17,9 +17,6 @@ hipError_t scan_exclusive_i32(const int32_t *in, int32_t *out, int64_t n_max, co
                               int32_t *tile_sums, int32_t *total_out, int32_t add_base,
                               hipStream_t s);
 
-// sums[0..nb) -> exclusive prefixes in place; sums[nb] = *total_out (nullable) = total.
-hipError_t scan_sums_inplace(int32_t *sums, int nb, int32_t *total_out, hipStream_t s);
-
 // ---- sample.hip (Algorithm 1, selection step) -------------------------------------------------
 // ballots: scratch uint64[ceil(B/64)]; tile_sums: scratch int32[scan_tiles(B)+1].
 // epoch_dev (nullable): the epoch index is read from device memory instead of `epoch`.
@@ -34,7 +31,7 @@ struct StaticSplit {       // inner / boundary split of the static CSR, built on
   int32_t *inner_ptr;      // int32[n_in+1]     inner entries before row v
   int32_t *bd_ptr;         // int32[n_in+1]     boundary entries before row v
   int32_t *in_col;         // int32[e_in]       inner entries, row-major
-  int32_t *in_row;         // int32[e_in]       their rows
+  int32_t *in_bdp;         // int32[e_in]       bd_ptr of their rows (boundary entries before the row)
   int32_t *bd_b;           // int32[e_bd]       boundary entries (boundary id), row-major
   int32_t *bd_row;         // int32[e_bd]       their rows
 };
@@ -47,16 +44,17 @@ hipError_t degree_rsqrt(const int32_t *deg, int32_t n, float *dis, hipStream_t s
 hipError_t build_sampled_csr(int32_t n_in, int64_t e_in, int64_t e_bd, const StaticSplit &sp,
                              const uint64_t *ballots, const int32_t *remap, int32_t *kpos, int32_t *tile_sums,
                              int32_t *row_ptr, int32_t *col_idx, int32_t *nnz, hipStream_t s);
-// hlen: scratch int32[n_halo]; tile_sums: scratch int32[scan_tiles(n_halo)+1].
+// kept_counts: scratch int32[kept_counts_size(n_halo)].
 // static_rows: write the rows of the inner nodes (the transposed inner-inner block, the same every
 // epoch: a destination that already holds them can skip it); kept_rows: write the rows of the kept
 // boundary nodes.
 hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
                                 const int32_t *t_in_ptr, const int32_t *t_in_col,
                                 const int32_t *halo_ptr, const int32_t *halo_col,
-                                const int32_t *kept_ids, const int32_t *n_kept, int32_t *hlen,
-                                int32_t *tile_sums, int32_t *t_row_ptr, int32_t *t_col_idx,
+                                const int32_t *kept_ids, const int32_t *n_kept,
+                                int32_t *kept_counts, int32_t *t_row_ptr, int32_t *t_col_idx,
                                 bool static_rows, bool kept_rows, hipStream_t s);
+inline int64_t kept_counts_size(int64_t n_halo) { return (int64_t)scan_tiles(n_halo) * (1 + kScanTile / 256) + 8; }
 
 struct Dropout;  // defined with the GEMMs below
 
@@ -119,12 +117,16 @@ hipError_t pad_rows(int32_t n_rows, int32_t d, int32_t ld, const float *src, flo
 // W on the matrix cores while other workgroups of the same compute unit keep gathering.  Rows cut
 // into several segments must have been finished before by spmm_fwd(..., long_rows_only = true).
 // Needs d_in % 4 == 0 and 64 < d_in <= 128 (spmm_gemm_fwd_supported).
+// concat_self: the update of the mean-aggregator layer, H_out = act([A | H_in] W) with W [2 d_in, d_out]
+// (neighbour half first): the tile is multiplied by W_n, overwritten with the rows' own features and
+// multiplied by W_s into the same accumulators; needs d_out <= 256 (spmm_gemm_fwd_concat_supported).
 bool spmm_gemm_fwd_supported(int32_t d_in);
+bool spmm_gemm_fwd_concat_supported(int32_t d_in, int32_t d_out);
 hipError_t spmm_gemm_fwd(const SegPlan &plan, int32_t n_in, int32_t d_in, int32_t d_out, const int32_t *row_ptr,
                          const int32_t *col_idx, const float *w_col, const float *row_scale,
                          const float *H_in, const float *Hu, float *partials, float *A,
                          const SpmmRowPart &part, const float *W, float *H_out, bool relu,
-                         const Dropout &drop, hipStream_t s);
+                         const Dropout &drop, hipStream_t s, bool concat_self = false);
 // For stacked column u < n_in + *n_kept:  g = sum_{v in t_row u} w_col[v] dA[v,:];
 //   u <  n_in: dH_in[u,:] = row_scale[u] * (init[u,:] + g)  (zeroed where mask_src[u,:] <= 0 if given)
 //   u >= n_in: dhalo[u-n_in,:] = s_halo * dis_halo[kept_ids[u-n_in]] * g   (skipped if dhalo null)

@@ -19,7 +19,7 @@ constexpr int kSampleIters = kScanTile / kSampleThreads;  // 8 wave-words per wa
 constexpr int kWordsPerTile = kScanTile / kWave;          // 32
 
 // Pass 1: keep flags as one 64-bit ballot word per 64 consecutive boundary nodes, and the
-// number of kept nodes per tile.
+// number of kept nodes per tile (tile_sums[tile], raw counts).
 __global__ void __launch_bounds__(kSampleThreads)
 sample_flags_kernel(const int64_t *__restrict__ halo_gid, int32_t n_halo, uint32_t k0, uint32_t k1,
                     uint32_t epoch, const uint32_t *__restrict__ epoch_dev, uint32_t part_id,
@@ -46,14 +46,18 @@ sample_flags_kernel(const int64_t *__restrict__ halo_gid, int32_t n_halo, uint32
   if (threadIdx.x == 0) tile_sums[blockIdx.x] = total;
 }
 
-// Pass 3: rank of every kept node = tile offset + kept nodes in earlier words of the tile +
-// kept lanes below it in its own word.
+// Pass 2: rank of every kept node = kept nodes in earlier tiles (summed by the block itself) +
+// kept nodes in earlier words of the tile + kept lanes below it in its own word.  Block 0 also
+// writes the total.
 __global__ void __launch_bounds__(kSampleThreads)
 sample_write_kernel(int32_t n_halo, const uint64_t *__restrict__ ballots,
-                    const int32_t *__restrict__ tile_offsets, int32_t *__restrict__ kept_ids,
-                    int32_t *__restrict__ remap) {
+                    const int32_t *__restrict__ tile_counts, int32_t *__restrict__ kept_ids,
+                    int32_t *__restrict__ remap, int32_t *__restrict__ n_kept) {
   __shared__ int word_prefix[kWordsPerTile];
   const int lane = lane_id();
+  int total = 0;
+  const int base = tiles_before<kSampleThreads>(tile_counts, blockIdx.x, gridDim.x, blockIdx.x == 0 ? &total : nullptr);
+  if (blockIdx.x == 0 && threadIdx.x == 0) *n_kept = total;
   const int64_t word0 = (int64_t)blockIdx.x * kWordsPerTile;
   const int64_t n_words = ((int64_t)n_halo + kWave - 1) / kWave;
   if (threadIdx.x < kWave) {
@@ -63,7 +67,6 @@ sample_write_kernel(int32_t n_halo, const uint64_t *__restrict__ ballots,
     if (threadIdx.x < kWordsPerTile) word_prefix[threadIdx.x] = inc - c;
   }
   __syncthreads();
-  const int base = tile_offsets[blockIdx.x];
 #pragma unroll
   for (int it = 0; it < kSampleIters; ++it) {
     const int local = it * kSampleThreads + threadIdx.x;
@@ -91,10 +94,7 @@ hipError_t sample_boundary(const int64_t *halo_gid, int32_t n_halo, uint64_t see
                                                     threshold, ballots, tile_sums);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  e = scan_sums_inplace(tile_sums, nb, n_kept, s);
-  if (e != hipSuccess) return e;
-  if (n_halo > 0)
-    sample_write_kernel<<<nb, kSampleThreads, 0, s>>>(n_halo, ballots, tile_sums, kept_ids, remap);
+  sample_write_kernel<<<nb, kSampleThreads, 0, s>>>(n_halo, ballots, tile_sums, kept_ids, remap, n_kept);
   return hipGetLastError();
 }
 

@@ -71,11 +71,6 @@ scan_tile_apply_kernel(const int32_t *__restrict__ in, int32_t *__restrict__ out
   }
 }
 
-hipError_t scan_sums_inplace(int32_t *sums, int nb, int32_t *total_out, hipStream_t s) {
-  scan_sums_kernel<<<1, 1024, 0, s>>>(sums, nb, total_out);
-  return hipGetLastError();
-}
-
 hipError_t scan_exclusive_i32(const int32_t *in, int32_t *out, int64_t n_max, const int32_t *n_dev,
                               int32_t *tile_sums, int32_t *total_out, int32_t add_base,
                               hipStream_t s) {

@@ -112,4 +112,20 @@ def widest():
     return _finish("edge-widest", w.part, [2048, 1022, 511, 3], 0, 18)
 
 
-EDGE = {"e-nobd": no_boundary, "e-max": widest, "e-nobdw": no_boundary_wide, "e-narrow": narrow_first, "e-star": star, "e-starw": star_wide, "e-single": single_node, "e-wide": wide_odd}
+def dense_rows():
+    """Rows of about 65 entries (a circulant of 60 neighbours plus boundary nodes of 20 neighbours each)
+    and a 96 -> 172 first layer: long enough rows that the mean-aggregator layer aggregates and
+    updates in one kernel, an output of two column tiles (128 + 44), depth padding from 96 to 128,
+    and a 1500-row partition that leaves a ragged last tile of 28 rows."""
+    rng = np.random.Generator(np.random.PCG64(19))
+    n, nb = 1500, 300
+    offs = np.concatenate([np.arange(1, 31), -np.arange(1, 31)])
+    src = np.repeat(np.arange(n), offs.size)
+    dst = (src + np.tile(offs, n)) % n
+    src_bd = rng.integers(0, n, size=nb * 20)
+    dst_gid = 5000 + np.repeat(np.arange(nb), 20)
+    part = partition_from_entries(4, n, src, dst, src_bd, dst_gid, halo_full_degree=lambda g, inc: inc + 7)
+    return _finish("edge-dense-rows", part, [96, 172, 128, 6], 0, 19)
+
+
+EDGE = {"e-dense": dense_rows, "e-nobd": no_boundary, "e-max": widest, "e-nobdw": no_boundary_wide, "e-narrow": narrow_first, "e-star": star, "e-starw": star_wide, "e-single": single_node, "e-wide": wide_odd}

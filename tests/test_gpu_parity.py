@@ -42,9 +42,10 @@ FULL = [(2, 1, [1.0, 0.1, 0.01], 0), (3, 1, [0.1, 0.01, 1.0], 0), (4, 1, [0.1, 0
 # degenerate shapes (tests/edge_workloads.py): empty boundary, hub rows, one node, odd widths
 EDGES = [("e-nobd", 1, [0.5, 1.0], 0), ("e-star", 1, [0.5, 0.0, 1.0], 1), ("e-single", 1, [0.5, 0.0, 1.0], 2),
          ("e-wide", 1, [0.5], 3), ("e-starw", 1, [0.5, 0.0, 1.0], 4),
-         ("e-nobdw", 1, [0.5], 5), ("e-max", 1, [0.5], 6), ("e-narrow", 1, [0.5, 1.0], 7)]
+         ("e-nobdw", 1, [0.5], 5), ("e-max", 1, [0.5], 6), ("e-narrow", 1, [0.5, 1.0], 7), ("e-dense", 1, [0.5], 8)]
 # the same matrix for the GraphSAGE-mean layer (layer_kind 1), thinner
-SAGE = [(1, 1, [0.1, 1.0, 0.0], 0), ("e-star", 1, [0.5], 1), ("e-wide", 1, [0.5], 3), (2, 16, [0.1], 1),
+SAGE = [(1, 1, [0.1, 1.0, 0.0], 0), ("e-star", 1, [0.5], 1), ("e-wide", 1, [0.5], 3), ("e-dense", 1, [0.5, 1.0], 8),
+        (2, 16, [0.1], 1),
         (3, 32, [0.1], 2), (4, 16, [0.1], 3), (2, 1, [0.1], 0), (3, 1, [0.1], 0), (4, 1, [0.1], 0), (5, 1, [0.1], 0)]
 CASES = [(c, s, p, e, 0) for (c, s, ps, e) in EDGES + SMALL + FULL for p in ps] + \
         [(c, s, p, e, 1) for (c, s, ps, e) in SAGE for p in ps]
@@ -590,10 +591,10 @@ def test_graph_replay_equals_eager_epochs(cfg, scale, kind, cached):
 
 @pytest.mark.parametrize("cfg,scale,kind,q", [(1, 1, 0, 0.5), (1, 1, 1, 0.3), (2, 16, 0, 0.3), (3, 32, 0, 0.5),
                                               (4, 16, 0, 0.1), (5, 64, 1, 0.5), (5, 1, 0, 0.5),
-                                              ("e-narrow", 1, 0, 0.3), (2, 1, 0, 0.3)],
+                                              ("e-narrow", 1, 0, 0.3), (2, 1, 0, 0.3), ("e-dense", 1, 1, 0.3)],
                          ids=["tiny-gcn-q0.5", "tiny-sage-q0.3", "cfg2s16-gcn-q0.3", "cfg3s32-gcn-q0.5",
                               "cfg4s16-gcn-q0.1", "cfg5s64-sage-q0.5", "cfg5-gcn-q0.5", "narrow-gcn-q0.3",
-                              "cfg2-gcn-q0.3"])
+                              "cfg2-gcn-q0.3", "dense-sage-q0.3"])
 def test_dropout_against_oracle(cfg, scale, kind, q):
     """Dropout on the hidden activations (training set-up of Section 4): same element draws as the
     oracle (bit-exact zero pattern away from ReLU ties), activations, loss and gradients within
