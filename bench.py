@@ -198,6 +198,8 @@ def run_workload(cfg, p, kind, steps, warmup, dropout=0.0, extras=False, cpu_bas
         "spmm_fwd_frac": fwd_bytes / (per_step_ms["spmm_fwd"] * 1e-3) / 1e9 / HBM_PEAK_GBS if per_step_ms["spmm_fwd"] else None,
         "spmm_bwd_frac": bwd_bytes / (per_step_ms["spmm_bwd"] * 1e-3) / 1e9 / HBM_PEAK_GBS if per_step_ms["spmm_bwd"] else None,
     }
+    classes["spmm_fwd_requested_GBps"] = fwd_req / (per_step_ms["spmm_fwd"] * 1e-3) / 1e9 if per_step_ms["spmm_fwd"] else None
+    classes["spmm_bwd_requested_GBps"] = bwd_req / (per_step_ms["spmm_bwd"] * 1e-3) / 1e9 if per_step_ms["spmm_bwd"] else None
     classes["spmm_fwd_long_row_pass_ms"] = long_ms      # part of spmm_fwd above
     for k, fl in gemm_flops.items():
         classes[k + "_TFLOPs"] = fl / (per_step_ms[k] * 1e-3) / 1e12 if per_step_ms[k] else None
@@ -254,6 +256,41 @@ def run_workload(cfg, p, kind, steps, warmup, dropout=0.0, extras=False, cpu_bas
             "spmm_fwd_algorithmic_bytes_per_step": fwd_c,
             "note": "layer 1 adds only the kept boundary entries of each row to the inner sum aggregated once at set-up",
         }
+        # ---- the ceiling of the aggregate's access pattern on this machine, measured beside it: a bare gather
+        # (bns_probe_gather) of as many uniformly random rows as a layer has entries, of the width the forward
+        # aggregates run at, from a table as large as the stacked features, as many rows per wavefront as the
+        # average row has entries.  The generator's graphs have no locality beyond their degree distribution,
+        # so no order of the same reads does better than this rate times the share of reads that hit in L2.
+        widths = [fw[l] for l in range(1, L + 1)]
+        d_probe = max(set(widths), key=widths.count)
+        if d_probe in (16, 32, 64, 128, 256):
+            n_rows = n_in + n_kept
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(220310983)
+            table = torch.randn(n_rows, d_probe, dtype=torch.float32, device=dev, generator=gen)
+            idx = torch.randint(0, n_rows, (nnz,), dtype=torch.int32, device=dev, generator=gen)
+            per_wave = max(1, round(nnz / n_in))
+            waves = (nnz + per_wave - 1) // per_wave
+            outp = torch.empty(waves, d_probe, dtype=torch.float32, device=dev)
+            for _ in range(3):
+                pkg.probe_gather(table, idx, per_wave, outp)
+            evp = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
+            torch.cuda.synchronize()
+            evp[0].record(stream)
+            for i in range(10):
+                pkg.probe_gather(table, idx, per_wave, outp)
+                evp[i + 1].record(stream)
+            torch.cuda.synchronize()
+            ms_g = statistics.median(evp[i].elapsed_time(evp[i + 1]) for i in range(10))
+            req = 4 * nnz + 4 * d_probe * nnz + 4 * d_probe * waves
+            ceiling = req / (ms_g * 1e-3) / 1e9
+            out["gather_ceiling"] = {
+                "requested_GBps": ceiling, "ms": ms_g, "rows_gathered": nnz, "row_floats": d_probe,
+                "table_MB": n_rows * d_probe * 4 / 1e6, "rows_per_wavefront": per_wave,
+                "note": "bare gather of uniformly random rows (index + row per entry + one row stored per wavefront), "
+                        "same loads in flight as the aggregate kernels; the aggregates' requested_GBps is to be read "
+                        "against this, their algorithmic GB/s against it times algorithmic / requested bytes"}
+            del table, idx, outp
         # ---- whole-step roofline: sum over kernel classes of max(compulsory bytes / HBM peak, flops / MFMA peak)
         gemm_bytes = {"gemm_fwd": sum(4 * n_in * (kw * dims[l - 1] + dims[l]) for l in range(1, L + 1) if l not in fused),
                       "gemm_dw": sum(4 * n_in * (kw * dims[l - 1] + dims[l]) for l in range(1, L + 1)),
@@ -354,7 +391,7 @@ def main():
         "kernel_classes": head["kernel_classes"],
         "sampling_overhead": head["sampling_overhead"],
     }
-    for k in ("ms_per_step_graph_replay", "cached_input_aggregate", "step_roofline", "memory"):
+    for k in ("ms_per_step_graph_replay", "cached_input_aggregate", "gather_ceiling", "step_roofline", "memory"):
         if k in head:
             out[k] = head[k]
     out["cpu_baseline"] = head.get("cpu_baseline")

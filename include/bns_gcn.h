@@ -300,6 +300,16 @@ bns_status bns_profile_enable(bns_ctx *ctx, uint32_t phase_mask, int32_t max_rec
 bns_status bns_profile_read(bns_ctx *ctx, double *ms_per_phase /* host [BNS_PHASE_COUNT] */,
                             int32_t *records_per_phase /* host [BNS_PHASE_COUNT] */);
 
+/* Instrumentation: the access pattern of the aggregate (Eq. 1) stripped of its arithmetic, to
+ * measure what this machine delivers for it.  Every wavefront sums per_wave rows of `table`
+ * (dev f32[n_rows*d], d in {16, 32, 64, 128, 256}) chosen by `idx` (dev int32[n_idx], values in
+ * [0, n_rows); the caller's responsibility, they are not checked) and stores the sum as one row:
+ * out dev f32[ceil(n_idx / per_wave) * d].  No weights, no row structure.  bench.py times it with
+ * as many uniformly random indices as a layer has entries, over a table as large as the layer's
+ * stacked features: the rate at which an aggregate on a graph without locality can gather. */
+bns_status bns_probe_gather(const float *table, int64_t n_rows, int32_t d, const int32_t *idx,
+                            int64_t n_idx, int32_t per_wave, float *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

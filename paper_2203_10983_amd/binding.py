@@ -21,7 +21,7 @@ NOALLOC_MAX_HALO = 1 << 22
 EXPORTED = ["bns_workspace_bytes", "bns_create", "bns_destroy", "bns_last_error",
             "bns_sample_boundary", "bns_sample_boundary_noalloc", "bns_build_sampled_csr", "bns_gcn_layer_fwd",
             "bns_gcn_layer_bwd", "bns_train_step", "bns_graph_capture", "bns_graph_replay", "bns_set_dropout", "bns_layer_plan", "bns_adam_update", "bns_cache_input_aggregate", "bns_ws_view",
-            "bns_profile_enable", "bns_profile_read"]
+            "bns_profile_enable", "bns_profile_read", "bns_probe_gather"]
 
 PHASES = ["sample", "build", "gather", "spmm_fwd", "gemm_fwd", "loss", "gemm_dw", "gemm_da",
           "spmm_bwd", "sgd", "spmm_long"]
@@ -104,6 +104,8 @@ def load_library():
     L.bns_ws_view.argtypes = [vp, i32, i32, C.POINTER(vp), C.POINTER(C.c_size_t)]
     L.bns_profile_enable.restype = i32
     L.bns_profile_enable.argtypes = [vp, u32, i32]
+    L.bns_probe_gather.restype = i32
+    L.bns_probe_gather.argtypes = [vp, C.c_int64, i32, vp, C.c_int64, i32, vp, vp]
     L.bns_profile_read.restype = i32
     L.bns_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
     _lib = L
@@ -140,6 +142,15 @@ def sample_boundary_noalloc(halo_gid, n_halo, part_id, seed, epoch, p, kept_ids,
                                        _ptr(remap), _ptr(n_kept), _stream())
     if st != 0:
         raise BnsError(st, L.bns_last_error(None).decode())
+
+
+def probe_gather(table, idx, per_wave, out):
+    """bns_probe_gather: sums of randomly indexed rows of `table` [n_rows, d], per_wave rows per wavefront."""
+    L = load_library()
+    st = L.bns_probe_gather(_ptr(table), table.shape[0], table.shape[1], _ptr(idx), idx.numel(), per_wave, _ptr(out),
+                            _stream())
+    if st != 0:
+        raise BnsError(st, "bns_probe_gather")
 
 
 class Context:
