@@ -233,10 +233,10 @@ int32_t bns_layer_plan(const bns_ctx *ctx, int32_t layer);
  * bns_train_step, relu != 0 in bns_gcn_layer_fwd) is zeroed with probability q and multiplied by
  * 1/(1-q) otherwise, and the backward calls scale the gradient of the surviving elements
  * accordingly (an element that is zero after dropout passes no gradient).  The draw is counter
- * based: word (row mod 4) of Philox-4x32-10 on the counter (row div 4, column,
- * part_id * 256 + layer, epoch) under the key (seed lo, seed hi xor 0x64726F70), with the seed and
- * epoch of the latest bns_sample_boundary / bns_train_step on this context; kept iff the word is
- * below floor((1-q) * 2^32).  Boundary features are used as handed in (their owners applied their
+ * based, one per element and built like the boundary draw: the first output word of Philox-4x32-10
+ * on the counter (row, column, part_id * 256 + layer, epoch) under the key (seed lo, seed hi xor
+ * 0x64726F70), with the seed and epoch of the latest bns_sample_boundary / bns_train_step on this
+ * context; kept iff the word is below floor((1-q) * 2^32).  Boundary features are used as handed in (their owners applied their
  * own dropout).  q = 0 (the default) switches dropout off; q outside [0, 1) -> BNS_EINVAL. */
 bns_status bns_set_dropout(bns_ctx *ctx, double q);
 

@@ -81,9 +81,10 @@ int64_t bnso_sample(uint64_t seed, uint32_t epoch, uint32_t part_id, double p,
 
 /* Dropout on hidden activations (Section 4 trains with dropout; the element-wise draw is this
  * build's reading): element (row, col) of the output of hidden layer `layer` is kept with
- * probability 1 - q.  The draw is word (row mod 4) of Philox-4x32-10 on the counter
- * (row div 4, col, part_id * 256 + layer, epoch) under the key (seed lo, seed hi xor 0x64726F70),
- * a stream separate from the boundary draw; keep  <=>  word < floor((1 - q) * 2^32). */
+ * probability 1 - q.  One draw per element, built like the boundary draw: the first output word
+ * of Philox-4x32-10 on the counter (row, col, part_id * 256 + layer, epoch) under the key
+ * (seed lo, seed hi xor 0x64726F70), a stream separate from the boundary draw;
+ * keep  <=>  word < floor((1 - q) * 2^32). */
 void bnso_dropout_mask(uint64_t seed, uint32_t epoch, uint32_t part_id, uint32_t layer,
                        int64_t n_rows, int64_t n_cols, double q, uint8_t *keep) {
   const uint64_t T = bnso_threshold(1.0 - q);
@@ -91,10 +92,10 @@ void bnso_dropout_mask(uint64_t seed, uint32_t epoch, uint32_t part_id, uint32_t
 #pragma omp parallel for schedule(static)
   for (int64_t row = 0; row < n_rows; ++row) {
     for (int64_t col = 0; col < n_cols; ++col) {
-      uint32_t ctr[4] = {(uint32_t)(row >> 2), (uint32_t)col, (part_id << 8) | layer, epoch};
+      uint32_t ctr[4] = {(uint32_t)row, (uint32_t)col, (part_id << 8) | layer, epoch};
       uint32_t out[4];
       bnso_philox4x32_10(ctr, key, out);
-      keep[row * n_cols + col] = (uint64_t)out[row & 3] < T ? 1 : 0;
+      keep[row * n_cols + col] = (uint64_t)out[0] < T ? 1 : 0;
     }
   }
 }

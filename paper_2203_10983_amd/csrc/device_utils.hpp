@@ -25,6 +25,16 @@ __device__ __forceinline__ void philox4x32_10(uint32_t &c0, uint32_t &c1, uint32
   }
 }
 
+// Dropout draw of element (row, col): kept iff the first Philox word on the counter (row, col, c2,
+// epoch) is below the threshold.  D: the Dropout parameter block of kernels.hpp.
+template <typename D>
+__device__ __forceinline__ bool dropout_keeps(const D &drop, int row, int col) {
+  uint32_t c0 = (uint32_t)row, c1 = (uint32_t)col, c2 = drop.c2;
+  uint32_t c3 = drop.epoch_dev ? *drop.epoch_dev : drop.epoch;
+  philox4x32_10(c0, c1, c2, c3, drop.k0, drop.k1);
+  return (uint64_t)c0 < drop.threshold;
+}
+
 // Inclusive prefix sum over the 64 lanes of a wavefront.
 __device__ __forceinline__ int wave_inclusive_scan(int x) {
   const int lane = lane_id();

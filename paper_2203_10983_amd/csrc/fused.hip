@@ -168,12 +168,6 @@ __global__ void __launch_bounds__(kFThreads, 6) __attribute__((amdgpu_num_sgpr(9
 #pragma unroll 1
       for (int q4 = 0; q4 < 4; ++q4) {
         const int row4 = row0 + wm + q4 * 8 + lhi * 4;
-        uint32_t u[4] = {0u, 0u, 0u, 0u};
-        if (f.relu && f.drop.scale != 0.f && row4 < a.n_split) {
-          u[0] = (uint32_t)(row4 >> 2); u[1] = (uint32_t)col; u[2] = f.drop.c2;
-          u[3] = f.drop.epoch_dev ? *f.drop.epoch_dev : f.drop.epoch;
-          philox4x32_10(u[0], u[1], u[2], u[3], f.drop.k0, f.drop.k1);
-        }
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
           const int row = row4 + rr;
@@ -181,7 +175,7 @@ __global__ void __launch_bounds__(kFThreads, 6) __attribute__((amdgpu_num_sgpr(9
             float x = acc[q4 * 4 + rr];
             if (f.relu) {
               x = fmaxf(x, 0.f);
-              if (f.drop.scale != 0.f) x = (uint64_t)u[rr] < f.drop.threshold ? x * f.drop.scale : 0.f;
+              if (f.drop.scale != 0.f) x = dropout_keeps(f.drop, row, col) ? x * f.drop.scale : 0.f;
             }
             f.H_out[(size_t)row * N + col] = x;
           }

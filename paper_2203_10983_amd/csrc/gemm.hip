@@ -136,8 +136,7 @@ __device__ __forceinline__ void store_ncontig(const FragN<COLS, NT> &f, float *_
 
 // EPI: 0 = store alpha * product, 1 = ReLU, 2 = zero where mask_src <= 0, alpha * product elsewhere
 // (ReLU/dropout mask of the backward pass), 3 = add to C, 4 = add to C then ReLU.  With EPI 1 or 4 and drop.scale != 0
-// the ReLU output goes through dropout: a lane owns four consecutive rows of one column per
-// accumulator quad, which is exactly one Philox call.
+// the ReLU output goes through dropout (one counter-based draw per element).
 // m_dev (nullable): the row count lives on the device (*m_dev <= M); tiles past it do nothing.
 // k_dev (nullable): the depth lives on the device (*k_dev <= K); steps past it contribute nothing.
 // A2 (nullable, k-contiguous A only): the operand is the concatenation [A | A2] along the depth,
@@ -265,12 +264,6 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         const int row4 = bm0 + wm + i * 32 + q4 * 8 + lhi * 4;  // a multiple of 4
-        uint32_t u[4] = {0u, 0u, 0u, 0u};
-        if ((EPI == 1 || EPI == 4) && drop.scale != 0.f && row4 < M) {
-          u[0] = (uint32_t)(row4 >> 2); u[1] = (uint32_t)col; u[2] = drop.c2;
-          u[3] = drop.epoch_dev ? *drop.epoch_dev : drop.epoch;
-          philox4x32_10(u[0], u[1], u[2], u[3], drop.k0, drop.k1);
-        }
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
           const int row = row4 + rr;
@@ -279,7 +272,7 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
             if (EPI == 3 || EPI == 4) x += Cd[(size_t)row * ldc + col];
             if (EPI == 1 || EPI == 4) {
               x = fmaxf(x, 0.f);
-              if (drop.scale != 0.f) x = (uint64_t)u[rr] < drop.threshold ? x * drop.scale : 0.f;
+              if (drop.scale != 0.f) x = dropout_keeps(drop, row, col) ? x * drop.scale : 0.f;
             }
             if (EPI == 2) x = mask_src[(size_t)row * ldc + col] > 0.f ? x * alpha : 0.f;
             if (EPI == 0) x = pad_col ? 0.f : x * alpha;

@@ -140,8 +140,8 @@ hipError_t spmm_bwd(const SegPlan &plan, int32_t n_in, int32_t n_halo, int32_t d
 
 // ---- gemm.hip (Eq. 2 and its backward; fp32 MFMA) ----------------------------------------------
 // Dropout on a hidden layer's output (training set-up of Section 4): element (row, col) is kept iff
-// word (row mod 4) of Philox-4x32-10 on the counter (row div 4, col, c2, epoch) under key (k0, k1)
-// is below `threshold`; kept elements are multiplied by `scale` = 1/(1-q).  scale == 0: no dropout.
+// the first word of Philox-4x32-10 on the counter (row, col, c2, epoch) under key (k0, k1) is below
+// `threshold`; kept elements are multiplied by `scale` = 1/(1-q).  scale == 0: no dropout.
 struct Dropout {
   uint64_t threshold = 0;
   float scale = 0.f;

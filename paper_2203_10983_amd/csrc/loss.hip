@@ -164,28 +164,20 @@ hipError_t loss_sigmoid_bce(int32_t n, int32_t C, const float *logits, const uin
   return hipGetLastError();
 }
 
-// one thread per (block of four rows, column): one Philox call covers its four elements
+// one thread and one draw per element
 __global__ void __launch_bounds__(kT)
 dropout_inplace_kernel(int n_rows, int d, float *__restrict__ H, const Dropout drop) {
-  const int64_t total = (int64_t)((n_rows + 3) / 4) * d;
+  const int64_t total = (int64_t)n_rows * d;
   const int64_t i = (int64_t)blockIdx.x * kT + threadIdx.x;
   if (i >= total) return;
-  const int r4 = (int)(i / d), col = (int)(i - (int64_t)r4 * d);
-  uint32_t u[4] = {(uint32_t)r4, (uint32_t)col, drop.c2, drop.epoch_dev ? *drop.epoch_dev : drop.epoch};
-  philox4x32_10(u[0], u[1], u[2], u[3], drop.k0, drop.k1);
-#pragma unroll
-  for (int rr = 0; rr < 4; ++rr) {
-    const int row = r4 * 4 + rr;
-    if (row < n_rows) {
-      float *p = H + (size_t)row * d + col;
-      *p = (uint64_t)u[rr] < drop.threshold ? *p * drop.scale : 0.f;
-    }
-  }
+  const int row = (int)(i / d), col = (int)(i - (int64_t)row * d);
+  const float x = H[i];
+  H[i] = dropout_keeps(drop, row, col) ? x * drop.scale : 0.f;
 }
 
 hipError_t dropout_inplace(int32_t n_rows, int32_t d, float *H, const Dropout &drop, hipStream_t s) {
   if (drop.scale == 0.f || n_rows <= 0) return hipSuccess;
-  const int64_t total = (int64_t)((n_rows + 3) / 4) * d;
+  const int64_t total = (int64_t)n_rows * d;
   dropout_inplace_kernel<<<(unsigned)((total + kT - 1) / kT), kT, 0, s>>>(n_rows, d, H, drop);
   return hipGetLastError();
 }

@@ -37,7 +37,7 @@ def test_python_philox_matches_the_published_vectors():
 
 @pytest.mark.parametrize("q", [0.1, 0.5])
 def test_mask_is_the_stated_draw(q):
-    """Element (row, col): word row%4 of Philox(counter (row//4, col, part*256+layer, epoch),
+    """Element (row, col): first word of Philox(counter (row, col, part*256+layer, epoch),
     key (seed lo, seed hi ^ 'drop')) below floor((1-q) 2^32)."""
     seed, epoch, part, layer, n, d = (5 << 32) | 77, 9, 3, 2, 37, 19
     mask = orc.dropout_mask(seed, epoch, part, layer, n, d, q)
@@ -45,7 +45,7 @@ def test_mask_is_the_stated_draw(q):
     key = [seed & M32, ((seed >> 32) ^ 0x64726F70) & M32]
     for row in range(n):
         for col in range(d):
-            w = _philox_py([row >> 2, col, (part << 8) | layer, epoch], key)[row & 3]
+            w = _philox_py([row, col, (part << 8) | layer, epoch], key)[0]
             assert mask[row, col] == (1 if w < T else 0), (row, col)
 
 
