@@ -180,7 +180,7 @@ def run_workload(cfg, p, kind, steps, warmup, dropout=0.0, extras=False, cpu_bas
         with open(os.path.join(ROOT, src)) as fh:
             line = [ln for ln in fh if ln.strip().startswith("bench-traffic:")][-1]
         tr = json.loads(line.split("bench-traffic:", 1)[1])
-        if tr["workload"].startswith(f"config {w.cfg}:") and abs(tr["p"] - p) < 1e-12 and kind == 0 \
+        if tr["workload"] == f"config {w.cfg}: {w.name}" and abs(tr["p"] - p) < 1e-12 and kind == 0 \
                 and not tr.get("input_aggregate_cached", True):
             if tr.get("csrc_sha") == kernel_source_hash():
                 roof["traffic"] = tr["bytes_per_launch"].get(dom)
