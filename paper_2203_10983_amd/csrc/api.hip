@@ -38,7 +38,7 @@ struct Layout {
   float *dis_in, *dis_halo;
   StaticSplit split;
   // scratch shared by all calls
-  int32_t *tile_sums, *kept_counts;
+  int32_t *tile_sums, *kept_start;
   uint64_t *ballots;
   int32_t *kpos;
   float *Hu, *Hu2, *G0, *G1, *G2, *partials, *loss_partials;  // Hu2: boundary rows at the output width
@@ -166,7 +166,7 @@ size_t carve(Carver &c, const bns_partition_desc *p, const bns_model_desc *m, La
   w.split.bd_b = c.take<int32_t>(p->e_bd);
   w.split.bd_row = c.take<int32_t>(p->e_bd);
   w.tile_sums = c.take<int32_t>(scan_tiles(p->nnz0 + n_in + B) + 4);
-  w.kept_counts = c.take<int32_t>(kept_counts_size(B));
+  w.kept_start = c.take<int32_t>((int64_t)B + 1);
   w.ballots = c.take<uint64_t>((B + 63) / 64 + 1);
   w.kpos = c.take<int32_t>(p->e_bd + 1);
   w.Hu = c.take<float>(B * d_in_max);
@@ -493,7 +493,8 @@ bns_status sample_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, const uint32
   PhaseTimer t(ctx, BNS_PHASE_SAMPLE, s);
   BNS_TRY("sample_boundary",
           sample_boundary(ctx->part.halo_gid, ctx->part.n_halo, seed, epoch, epoch_dev, (uint32_t)ctx->part.part_id,
-                          threshold, ctx->ws.ballots, ctx->ws.tile_sums, kept_ids, remap, n_kept, s));
+                          threshold, ctx->ws.ballots, ctx->ws.tile_sums, kept_ids, remap, n_kept, ctx->part.halo_ptr,
+                          (int32_t)ctx->part.e_in, ctx->ws.kept_start, s));
   ctx->cur_kept = kept_ids;
   ctx->cur_remap = remap;
   ctx->cur_n_kept = n_kept;
@@ -512,7 +513,7 @@ bns_status build_impl(bns_ctx *ctx, int32_t *row_ptr, int32_t *col_idx, int32_t 
                             ctx->ws.tile_sums, row_ptr, col_idx, nnz, s));
   BNS_TRY("build_transposed_csr",
           build_transposed_csr(P.n_in, P.n_halo, P.e_in, P.t_in_ptr, P.t_in_col, P.halo_ptr, P.halo_col,
-                               ctx->cur_kept, ctx->cur_n_kept, ctx->ws.kept_counts,
+                               ctx->cur_kept, ctx->cur_n_kept, ctx->ws.kept_start,
                                t_row_ptr, t_col_idx,
                                // the workspace arrays hold the static rows since bns_create
                                !(t_row_ptr == ctx->ws.t_row_ptr && t_col_idx == ctx->ws.t_col_idx), true, s));
@@ -567,7 +568,7 @@ bns_status bns_create(bns_ctx **out, const bns_partition_desc *part, const bns_m
   // the rows of the inner nodes in the workspace's transposed CSR are the same in every epoch
   BNS_TRY("build_transposed_csr(static rows)",
           build_transposed_csr(part->n_in, part->n_halo, part->e_in, part->t_in_ptr, part->t_in_col, part->halo_ptr,
-                               part->halo_col, nullptr, nullptr, ctx->ws.kept_counts, ctx->ws.t_row_ptr,
+                               part->halo_col, nullptr, nullptr, ctx->ws.kept_start, ctx->ws.t_row_ptr,
                                ctx->ws.t_col_idx, true, false, s));
   BNS_TRY("set-up sync", hipStreamSynchronize(s));
   return BNS_OK;

@@ -213,75 +213,23 @@ hipError_t build_sampled_csr(int32_t n_in, int64_t e_in, int64_t e_bd, const Sta
 
 // ---------------------------------------------------------------------------------- transpose
 // Rows of the kept boundary nodes in the transposed CSR: kept node r (boundary node b =
-// kept_ids[r]) gets b's static list of inner neighbours.  Pass 1 counts the entries of every tile of
-// kScanTile kept nodes and of each of its kSubTiles pieces; pass 2 runs one block per piece: the row
-// starts follow from the counts of the tiles before (summed by the block itself), of the pieces
-// before in the same tile and a scan inside the piece; pass 3 copies the lists, eight lanes each
-// (a pass of its own: copying inside pass 2 left too few lanes busy and took three times as long).
-constexpr int kRowsPerThread = kScanTile / kThreads;
-constexpr int kSubTiles = kScanTile / kThreads;            // pieces of kThreads rows
-constexpr int kLanesPerPiece = kThreads / kSubTiles;       // threads of pass 1 that cover one piece
-static_assert(kLanesPerPiece == 32, "pass 1 folds the counts of a piece inside half a wavefront");
-
-// counts: int32[nb * (1 + kSubTiles)]: nb tile counts, then kSubTiles piece counts per tile
-__global__ void __launch_bounds__(kThreads)
-kept_len_counts_kernel(const int32_t *__restrict__ n_kept, const int32_t *__restrict__ kept_ids,
-                       const int32_t *__restrict__ halo_ptr, int32_t *__restrict__ counts) {
-  const int n = *n_kept;
-  const int r0 = blockIdx.x * kScanTile + threadIdx.x * kRowsPerThread;
-  int sum = 0;
-#pragma unroll
-  for (int k = 0; k < kRowsPerThread; ++k)
-    if (r0 + k < n) {
-      const int b = kept_ids[r0 + k];
-      sum += halo_ptr[b + 1] - halo_ptr[b];
-    }
-  int piece = sum;  // the 32 consecutive threads of a piece sit in one half of a wavefront
-#pragma unroll
-  for (int off = kLanesPerPiece / 2; off > 0; off >>= 1) piece += __shfl_xor(piece, off, kWave);
-  if (threadIdx.x % kLanesPerPiece == 0)
-    counts[gridDim.x + blockIdx.x * kSubTiles + threadIdx.x / kLanesPerPiece] = piece;
-  int total;
-  block_exclusive_scan<kThreads>(sum, &total);
-  if (threadIdx.x == 0) counts[blockIdx.x] = total;
-}
-
-__global__ void __launch_bounds__(kThreads)
-kept_row_starts_kernel(const int32_t *__restrict__ n_kept, const int32_t *__restrict__ kept_ids,
-                       const int32_t *__restrict__ halo_ptr, const int32_t *__restrict__ counts, int32_t nb,
-                       int32_t first, int32_t *__restrict__ t_tail_ptr) {
-  const int n = *n_kept;
-  const int tile = blockIdx.x / kSubTiles, sub = blockIdx.x % kSubTiles;
-  const int row0 = tile * kScanTile + sub * kThreads;
-  if (n == 0 && blockIdx.x == 0 && threadIdx.x == 0) t_tail_ptr[0] = first;
-  if (row0 >= n) return;
-  int base = first + tiles_before<kThreads>(counts, tile, nb, nullptr);
-  for (int i = 0; i < sub; ++i) base += counts[nb + tile * kSubTiles + i];
-  const int r = row0 + threadIdx.x;
-  int len = 0;
-  if (r < n) {
-    const int b = kept_ids[r];
-    len = halo_ptr[b + 1] - halo_ptr[b];
-  }
-  int total;
-  const int dst = base + block_exclusive_scan<kThreads>(len, &total);
-  if (r < n) {
-    t_tail_ptr[r] = dst;
-    if (r == n - 1) t_tail_ptr[n] = dst + len;
-  }
-}
-
-// Eight lanes copy one kept boundary node's list of inner rows.
+// kept_ids[r]) gets b's static list of inner neighbours.  Where each row starts was settled by the
+// sampler (a prefix sum of the list lengths in kept order, kept_start[0..n_kept]); eight lanes copy
+// one list and write the row's start.
 __global__ void __launch_bounds__(kThreads)
 kept_rows_fill_kernel(const int32_t *__restrict__ n_kept, const int32_t *__restrict__ kept_ids,
                       const int32_t *__restrict__ halo_ptr, const int32_t *__restrict__ halo_col,
-                      const int32_t *__restrict__ t_tail_ptr, int32_t *__restrict__ t_col_idx) {
+                      const int32_t *__restrict__ kept_start, int32_t *__restrict__ t_tail_ptr,
+                      int32_t *__restrict__ t_col_idx) {
   const int r = (blockIdx.x * kThreads + threadIdx.x) >> 3;
   const int sub = threadIdx.x & 7;
-  if (r >= *n_kept) return;
+  const int n = *n_kept;
+  if (r == 0 && sub == 0) t_tail_ptr[n] = kept_start[n];
+  if (r >= n) return;
   const int b = kept_ids[r];
   const int src = halo_ptr[b], len = halo_ptr[b + 1] - src;
-  const int dst = t_tail_ptr[r];
+  const int dst = kept_start[r];
+  if (sub == 0) t_tail_ptr[r] = dst;
   for (int i = sub; i < len; i += 8) t_col_idx[dst + i] = halo_col[src + i];
 }
 
@@ -299,7 +247,7 @@ hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
                                 const int32_t *t_in_ptr, const int32_t *t_in_col,
                                 const int32_t *halo_ptr, const int32_t *halo_col,
                                 const int32_t *kept_ids, const int32_t *n_kept,
-                                int32_t *kept_counts, int32_t *t_row_ptr, int32_t *t_col_idx,
+                                const int32_t *kept_start, int32_t *t_row_ptr, int32_t *t_col_idx,
                                 bool static_rows, bool kept_rows, hipStream_t s) {
   // rows of inner nodes never change: the transpose of the inner-inner block (copied by a kernel,
   // so that the whole step stays a plain chain of kernel nodes under graph capture)
@@ -314,17 +262,9 @@ hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
   if (e != hipSuccess) return e;
   if (n_halo == 0 || !kept_rows) return hipSuccess;
   // rows of kept boundary nodes: their static lists of inner neighbours, in kept order
-  const int nb = scan_tiles(n_halo);
-  kept_len_counts_kernel<<<nb, kThreads, 0, s>>>(n_kept, kept_ids, halo_ptr, kept_counts);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  kept_row_starts_kernel<<<nb * kSubTiles, kThreads, 0, s>>>(n_kept, kept_ids, halo_ptr, kept_counts, nb,
-                                                             (int32_t)e_in, t_row_ptr + n_in);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
   const int64_t threads = (int64_t)n_halo * 8;
   kept_rows_fill_kernel<<<(unsigned)((threads + kThreads - 1) / kThreads), kThreads, 0, s>>>(
-      n_kept, kept_ids, halo_ptr, halo_col, t_row_ptr + n_in, t_col_idx);
+      n_kept, kept_ids, halo_ptr, halo_col, kept_start, t_row_ptr + n_in, t_col_idx);
   return hipGetLastError();
 }
 

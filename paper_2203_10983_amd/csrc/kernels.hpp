@@ -18,12 +18,15 @@ hipError_t scan_exclusive_i32(const int32_t *in, int32_t *out, int64_t n_max, co
                               hipStream_t s);
 
 // ---- sample.hip (Algorithm 1, selection step) -------------------------------------------------
-// ballots: scratch uint64[ceil(B/64)]; tile_sums: scratch int32[scan_tiles(B)+1].
-// epoch_dev (nullable): the epoch index is read from device memory instead of `epoch`.
+// ballots: scratch uint64[ceil(B/64)]; tile_sums: scratch int32[2 * scan_tiles(B) + 1] (half of it
+// without kept_start).  epoch_dev (nullable): the epoch index is read from device memory instead of
+// `epoch`.  halo_ptr + kept_start (both nullable): kept_start[r] = first + the summed lengths
+// halo_ptr[b+1] - halo_ptr[b] of the kept nodes before the r-th one, r = 0..n_kept (int32[B+1]): the
+// row starts of the kept nodes in the transposed subgraph, which build_transposed_csr reads.
 hipError_t sample_boundary(const int64_t *halo_gid, int32_t n_halo, uint64_t seed, uint32_t epoch,
                            const uint32_t *epoch_dev, uint32_t part_id, uint64_t threshold, uint64_t *ballots,
                            int32_t *tile_sums, int32_t *kept_ids, int32_t *remap, int32_t *n_kept,
-                           hipStream_t s);
+                           const int32_t *halo_ptr, int32_t first, int32_t *kept_start, hipStream_t s);
 
 // ---- build_csr.hip (Algorithm 1, subgraph step) -----------------------------------------------
 struct StaticSplit {       // inner / boundary split of the static CSR, built once
@@ -44,7 +47,7 @@ hipError_t degree_rsqrt(const int32_t *deg, int32_t n, float *dis, hipStream_t s
 hipError_t build_sampled_csr(int32_t n_in, int64_t e_in, int64_t e_bd, const StaticSplit &sp,
                              const uint64_t *ballots, const int32_t *remap, int32_t *kpos, int32_t *tile_sums,
                              int32_t *row_ptr, int32_t *col_idx, int32_t *nnz, hipStream_t s);
-// kept_counts: scratch int32[kept_counts_size(n_halo)].
+// kept_start: the row starts of the kept nodes as sample_boundary left them (int32[n_kept+1]).
 // static_rows: write the rows of the inner nodes (the transposed inner-inner block, the same every
 // epoch: a destination that already holds them can skip it); kept_rows: write the rows of the kept
 // boundary nodes.
@@ -52,9 +55,8 @@ hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
                                 const int32_t *t_in_ptr, const int32_t *t_in_col,
                                 const int32_t *halo_ptr, const int32_t *halo_col,
                                 const int32_t *kept_ids, const int32_t *n_kept,
-                                int32_t *kept_counts, int32_t *t_row_ptr, int32_t *t_col_idx,
+                                const int32_t *kept_start, int32_t *t_row_ptr, int32_t *t_col_idx,
                                 bool static_rows, bool kept_rows, hipStream_t s);
-inline int64_t kept_counts_size(int64_t n_halo) { return (int64_t)scan_tiles(n_halo) * (1 + kScanTile / 256) + 8; }
 
 struct Dropout;  // defined with the GEMMs below
 

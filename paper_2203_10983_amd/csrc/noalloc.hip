@@ -81,7 +81,7 @@ extern "C" bns_status bns_sample_boundary_noalloc(const int64_t *halo_gid, int32
   int32_t *tile_sums = reinterpret_cast<int32_t *>(base + kBallotBytesAligned);
   const uint64_t threshold = (uint64_t)std::floor(p * 4294967296.0);
   e = sample_boundary(halo_gid, n_halo, seed, epoch, nullptr, (uint32_t)part_id, threshold, ballots, tile_sums,
-                      kept_ids, remap, n_kept, static_cast<hipStream_t>(stream));
+                      kept_ids, remap, n_kept, nullptr, 0, nullptr, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) {
     (void)hipGetLastError();
     return fail(BNS_EHIP, "sample_boundary: ", hipGetErrorString(e));
