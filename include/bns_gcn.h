@@ -282,8 +282,10 @@ bns_status bns_ws_view(const bns_ctx *ctx, bns_view which, int32_t layer, void *
  * phase the summed milliseconds and the number of brackets since the last read, and clears them.
  * Events are host objects: no device memory is allocated. */
 typedef enum {
-  BNS_PHASE_SAMPLE = 0,   /* sample_boundary kernels                       */
-  BNS_PHASE_BUILD = 1,    /* sampled CSR + transposed CSR                  */
+  BNS_PHASE_SAMPLE = 0,   /* sample_boundary kernels; in bns_train_step on a small partition (at most 4096
+                             boundary nodes, 8192 boundary entries, 16384 inner nodes + inner entries) the one
+                             launch that runs the selection and the subgraph step together               */
+  BNS_PHASE_BUILD = 1,    /* sampled CSR + transposed CSR (no bracket where the sample phase covers it)  */
   BNS_PHASE_GATHER = 2,   /* gather of kept boundary features (x 1/p)      */
   BNS_PHASE_SPMM_FWD = 3, /* aggregate                                     */
   BNS_PHASE_GEMM_FWD = 4, /* update  A W                                   */

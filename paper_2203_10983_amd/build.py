@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbns_gcn.so")
-SOURCES = ["scan.hip", "sample.hip", "build_csr.hip", "spmm.hip", "fused.hip", "gemm.hip", "loss.hip", "api.hip", "noalloc.hip", "probe.hip"]
+SOURCES = ["scan.hip", "sample.hip", "small.hip", "build_csr.hip", "spmm.hip", "fused.hip", "gemm.hip", "loss.hip", "api.hip", "noalloc.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          # packed fp32 instructions are kept out of every kernel

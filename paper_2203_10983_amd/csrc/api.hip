@@ -524,6 +524,37 @@ bns_status build_impl(bns_ctx *ctx, int32_t *row_ptr, int32_t *col_idx, int32_t 
   return BNS_OK;
 }
 
+// Selection step + subgraph step of a training step, into the workspace arrays: one launch for a
+// small partition (timed as the sample phase), else the two calls above.
+bns_status sample_and_build_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, const uint32_t *epoch_dev, double p,
+                                 hipStream_t s) {
+  Layout &w = ctx->ws;
+  const bns_partition_desc &P = ctx->part;
+  if (!sample_build_small_fits(P.n_in, P.n_halo, P.e_in, P.e_bd)) {
+    const bns_status st = sample_impl(ctx, seed, epoch, epoch_dev, p, w.kept_ids, w.remap, w.counters, s);
+    if (st != BNS_OK) return st;
+    return build_impl(ctx, w.row_ptr, w.col_idx, w.t_row_ptr, w.t_col_idx, w.counters + 1, s);
+  }
+  const uint64_t threshold = (uint64_t)std::floor(p * 4294967296.0);
+  PhaseTimer t(ctx, BNS_PHASE_SAMPLE, s);
+  BNS_TRY("sample_build_small",
+          sample_build_small(P.halo_gid, P.n_halo, seed, epoch, epoch_dev, (uint32_t)P.part_id, threshold, w.ballots,
+                             w.kept_ids, w.remap, w.counters, w.kept_start, P.n_in, P.e_in, P.e_bd, w.split, w.kpos,
+                             w.row_ptr, w.col_idx, w.counters + 1, P.halo_ptr, P.halo_col, w.t_row_ptr, w.t_col_idx,
+                             s));
+  ctx->cur_kept = w.kept_ids;
+  ctx->cur_remap = w.remap;
+  ctx->cur_n_kept = w.counters;
+  ctx->cur_seed = seed;
+  ctx->cur_epoch = epoch;
+  ctx->cur_epoch_dev = epoch_dev;
+  ctx->cur_row_ptr = w.row_ptr;
+  ctx->cur_col_idx = w.col_idx;
+  ctx->cur_t_row_ptr = w.t_row_ptr;
+  ctx->cur_t_col_idx = w.t_col_idx;
+  return BNS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -653,9 +684,7 @@ static bns_status train_step_impl(bns_ctx *ctx, uint64_t seed, uint32_t epoch, c
   hipStream_t s = static_cast<hipStream_t>(stream);
   Layout &w = ctx->ws;
 
-  bns_status st = sample_impl(ctx, seed, epoch, epoch_dev, p, w.kept_ids, w.remap, w.counters, s);
-  if (st != BNS_OK) return st;
-  st = build_impl(ctx, w.row_ptr, w.col_idx, w.t_row_ptr, w.t_col_idx, w.counters + 1, s);
+  bns_status st = sample_and_build_impl(ctx, seed, epoch, epoch_dev, p, s);
   if (st != BNS_OK) return st;
 
   const float *H_prev = X;

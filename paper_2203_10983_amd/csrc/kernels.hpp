@@ -58,6 +58,22 @@ hipError_t build_transposed_csr(int32_t n_in, int32_t n_halo, int64_t e_in,
                                 const int32_t *kept_start, int32_t *t_row_ptr, int32_t *t_col_idx,
                                 bool static_rows, bool kept_rows, hipStream_t s);
 
+// ---- small.hip: selection step + subgraph step of a small partition in one launch -------------
+// One workgroup runs the stages of sample_boundary, build_sampled_csr and the kept rows of
+// build_transposed_csr back to back and writes the same arrays (t_row_ptr / t_col_idx must already
+// hold the static rows of the inner nodes).  Only for sizes within the limits below, where the six
+// launches of the general path cost more than the work itself.
+constexpr int kSmallMaxHalo = 4096;              // boundary nodes
+constexpr int kSmallMaxBoundaryEntries = 8192;   // entries with a boundary column
+constexpr int kSmallMaxInnerWork = 16384;        // inner nodes + inner entries
+bool sample_build_small_fits(int32_t n_in, int32_t n_halo, int64_t e_in, int64_t e_bd);
+hipError_t sample_build_small(const int64_t *halo_gid, int32_t n_halo, uint64_t seed, uint32_t epoch,
+                              const uint32_t *epoch_dev, uint32_t part_id, uint64_t threshold, uint64_t *ballots,
+                              int32_t *kept_ids, int32_t *remap, int32_t *n_kept, int32_t *kept_start,
+                              int32_t n_in, int64_t e_in, int64_t e_bd, const StaticSplit &sp, int32_t *kpos,
+                              int32_t *row_ptr, int32_t *col_idx, int32_t *nnz, const int32_t *halo_ptr,
+                              const int32_t *halo_col, int32_t *t_row_ptr, int32_t *t_col_idx, hipStream_t s);
+
 struct Dropout;  // defined with the GEMMs below
 
 // ---- spmm.hip (Eq. 1 in the sampled form of Appendix A, and its transpose) ---------------------

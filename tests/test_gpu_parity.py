@@ -409,6 +409,41 @@ def test_train_step_with_cached_input_aggregate(case):
         c.ctx.cache_input_aggregate(None)
 
 
+@pytest.mark.parametrize("cfg,scale,one_launch", [(1, 1, True), ("e-star", 1, True), (3, 32, False)],
+                         ids=["tiny", "e-star", "cfg3-s32"])
+def test_which_path_builds_the_subgraph(cfg, scale, one_launch):
+    """A training step of a small partition runs the selection and subgraph steps as one launch (timed
+    as the sample phase: no record in the build phase), a larger one as the six launches of the
+    general path; the integer results of both are compared with the oracle by the end-to-end test,
+    and here against the stand-alone calls, which always take the general path."""
+    c = _Case.get(cfg, scale, 0)
+    w, P, torch, pkg = c.w, c.w.part, c.torch, c.pkg
+    L, p, epoch = w.n_layers, 0.5, 3
+    f32 = dict(dtype=torch.float32, device=c.dev)
+    dW = [torch.empty_like(x) for x in c.W]
+    dhalo = [None] + [torch.zeros(P.n_halo + 1, w.dims[l], **f32) for l in range(1, L)]
+    loss = torch.zeros(1, **f32)
+    c.ctx.profile_enable(0xFFFFFFFF, 64 * L + 64)
+    c.ctx.train_step(SAMPLING_SEED, epoch, p, c.X, c.halo_h, c.labels, c.W, dW, dhalo, loss, 0.0)
+    torch.cuda.synchronize()
+    phases = c.ctx.profile_read()
+    c.ctx.profile_enable(0, 0)
+    assert phases["sample"][1] == 1
+    assert phases["build"][1] == (0 if one_launch else 1)
+    view = lambda which: c.ctx.ws_tensor(which, 0, torch.int32).cpu().numpy().copy()  # noqa: E731
+    got = [view(v) for v in (pkg.VIEW_KEPT_IDS, pkg.VIEW_REMAP, pkg.VIEW_N_KEPT, pkg.VIEW_ROW_PTR, pkg.VIEW_COL_IDX,
+                             pkg.VIEW_T_ROW_PTR, pkg.VIEW_T_COL_IDX, pkg.VIEW_NNZ)]
+    out = _sample_and_build(c, p, epoch)
+    n_u, nnz = int(out["n_kept"][0]), int(out["nnz"][0])
+    assert int(got[2][0]) == n_u and int(got[7][0]) == nnz
+    assert np.array_equal(got[0][:n_u], out["kept"].cpu().numpy()[:n_u])
+    assert np.array_equal(got[1][:P.n_halo], out["remap"].cpu().numpy()[:P.n_halo])
+    assert np.array_equal(got[3], out["row_ptr"].cpu().numpy())
+    assert np.array_equal(got[4][:nnz], out["col_idx"].cpu().numpy()[:nnz])
+    assert np.array_equal(got[5][:P.n_in + n_u + 1], out["t_row_ptr"].cpu().numpy()[:P.n_in + n_u + 1])
+    assert np.array_equal(got[6][:nnz], out["t_col_idx"].cpu().numpy()[:nnz])
+
+
 @pytest.mark.parametrize("kind", [0, 1], ids=["gcn", "sage"])
 def test_sgd_trajectory_on_tiny(kind):
     """Algorithm 1, update step: three epochs of w <- w - lr * g with a fresh sample per epoch.
