@@ -177,7 +177,7 @@ __global__ void __launch_bounds__(kFThreads, 6) __attribute__((amdgpu_num_sgpr(9
               x = fmaxf(x, 0.f);
               if (f.drop.scale != 0.f) x = dropout_keeps(f.drop, row, col) ? x * f.drop.scale : 0.f;
             }
-            f.H_out[(size_t)row * N + col] = x;
+            __builtin_nontemporal_store(x, f.H_out + (size_t)row * N + col);  // streamed out, as the aggregate
           }
         }
       }

