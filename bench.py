@@ -332,7 +332,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", type=int, default=5, help="headline config 1..5 of BASELINE.json")
+    ap.add_argument("--workload", type=int, default=5, help="headline workload, 1..5")
     ap.add_argument("--p", type=float, default=0.1, help="sampling rate of the headline workload")
     ap.add_argument("--model", choices=["gcn", "sage"], default="gcn",
                     help="gcn: the GCN layer of the five configs; sage: GraphSAGE-mean, the paper's own model")

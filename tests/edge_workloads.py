@@ -128,4 +128,11 @@ def dense_rows():
     return _finish("edge-dense-rows", part, [96, 172, 128, 6], 0, 19)
 
 
-EDGE = {"e-dense": dense_rows, "e-nobd": no_boundary, "e-max": widest, "e-nobdw": no_boundary_wide, "e-narrow": narrow_first, "e-star": star, "e-starw": star_wide, "e-single": single_node, "e-wide": wide_odd}
+def degree_ordered():
+    """Workload 3 at 1/32 of its size with the inner nodes numbered by descending degree (the hub rows
+    first): local ids are the partitioner's choice, and every kernel must be indifferent to it."""
+    from bns_inputs import make_workload
+    return make_workload(3, scale=32, local_order="degree")
+
+
+EDGE = {"e-degree": degree_ordered, "e-dense": dense_rows, "e-nobd": no_boundary, "e-max": widest, "e-nobdw": no_boundary_wide, "e-narrow": narrow_first, "e-star": star, "e-starw": star_wide, "e-single": single_node, "e-wide": wide_odd}

@@ -42,7 +42,8 @@ FULL = [(2, 1, [1.0, 0.1, 0.01], 0), (3, 1, [0.1, 0.01, 1.0], 0), (4, 1, [0.1, 0
 # degenerate shapes (tests/edge_workloads.py): empty boundary, hub rows, one node, odd widths
 EDGES = [("e-nobd", 1, [0.5, 1.0], 0), ("e-star", 1, [0.5, 0.0, 1.0], 1), ("e-single", 1, [0.5, 0.0, 1.0], 2),
          ("e-wide", 1, [0.5], 3), ("e-starw", 1, [0.5, 0.0, 1.0], 4),
-         ("e-nobdw", 1, [0.5], 5), ("e-max", 1, [0.5], 6), ("e-narrow", 1, [0.5, 1.0], 7), ("e-dense", 1, [0.5], 8)]
+         ("e-nobdw", 1, [0.5], 5), ("e-max", 1, [0.5], 6), ("e-narrow", 1, [0.5, 1.0], 7), ("e-dense", 1, [0.5], 8),
+         ("e-degree", 1, [0.1], 2)]
 # the same matrix for the GraphSAGE-mean layer (layer_kind 1), thinner
 SAGE = [(1, 1, [0.1, 1.0, 0.0], 0), ("e-star", 1, [0.5], 1), ("e-wide", 1, [0.5], 3), ("e-dense", 1, [0.5, 1.0], 8),
         (2, 16, [0.1], 1),
