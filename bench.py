@@ -44,6 +44,41 @@ def kernel_source_hash():
     return h.hexdigest()[:16]
 
 
+def mfma_regimes():
+    """Issue rate of v_mfma_f32_32x32x2_f32 with nothing else in the loop, over wavefronts resident per SIMD
+    and independent accumulators per wavefront (one workgroup of 4 w wavefronts per compute unit gives w per
+    SIMD; two or three workgroups per compute unit reach 6 and 8)."""
+    import torch
+    import paper_2203_10983_amd as pkg
+    dev = torch.device("cuda:0")
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    stream = torch.cuda.current_stream()
+    out = torch.zeros(8 * cus, dtype=torch.float32, device=dev)
+    # (wavefronts per workgroup, workgroups per compute unit, accumulators)
+    cases = [(4, 1, 1), (4, 1, 2), (4, 1, 4), (8, 1, 1), (8, 1, 2), (8, 1, 4), (8, 1, 6), (4, 3, 4), (4, 4, 4), (16, 1, 4),
+             (4, 4, 1), (4, 4, 2), (16, 1, 1), (16, 1, 2), (8, 3, 2), (8, 4, 2), (16, 2, 1), (16, 2, 2), (4, 8, 2)]
+    rows = []
+    for wpb, bpc, n_acc in cases:
+        per_simd = wpb * bpc // 4
+        iters = max(200, 16000 // (per_simd * n_acc))
+        blocks = cus * bpc
+        for _ in range(2):
+            pkg.probe_mfma(n_acc, wpb, blocks, iters, out)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        torch.cuda.synchronize()
+        ev[0].record(stream)
+        for i in range(3):
+            pkg.probe_mfma(n_acc, wpb, blocks, iters, out)
+            ev[i + 1].record(stream)
+        torch.cuda.synchronize()
+        ms = statistics.median(ev[i].elapsed_time(ev[i + 1]) for i in range(3))
+        flops = 4096.0 * 8 * n_acc * iters * wpb * blocks
+        rows.append({"wavefronts_per_simd": per_simd, "accumulators": n_acc, "wavefronts_per_workgroup": wpb,
+                     "workgroups_per_cu": bpc, "ms": round(ms, 3), "TFLOPs": round(flops / ms / 1e9, 1)})
+    return {"metric": "issue rate of v_mfma_f32_32x32x2_f32, nothing else in the loop", "unit": "TFLOP/s",
+            "peak": FP32_MFMA_PEAK_TFLOPS, "compute_units": cus, "regimes": rows}
+
+
 def run_workload(cfg, p, kind, steps, warmup, dropout=0.0, extras=False, cpu_baseline=True, calibrate=False,
                  local_order="native"):
     """Times one workload; -> dict.  extras: also the graph-replay and the cached-input variants,
@@ -339,6 +374,9 @@ def main():
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="dropout rate on the hidden activations (the five workloads name none: default 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mfma-regimes", action="store_true",
+                    help="instead of a workload: time the bare fp32 matrix instruction (bns_probe_mfma) over wavefronts "
+                         "per SIMD x independent accumulators per wavefront and print the rates as one JSON line")
     ap.add_argument("--local-order", choices=["native", "degree"], default="native",
                     help="numbering of the partition's inner nodes: the generator's (default, what every reported figure "
                          "uses) or descending degree (the measurement of what node order does to the aggregates)")
@@ -352,6 +390,9 @@ def main():
         sys.exit("bench.py: this build runs one partition on ONE GPU; --gpus must be 1 "
                  "(no collectives or sharding are part of it)")
 
+    if args.mfma_regimes:
+        print(json.dumps(mfma_regimes()))
+        return
     kind = 1 if args.model == "sage" else 0
     head = run_workload(args.workload, args.p, kind, args.steps, args.warmup, dropout=args.dropout,
                         extras=not args.only, cpu_baseline=not args.no_cpu_baseline, calibrate=args.calibrate_copy,

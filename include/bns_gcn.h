@@ -312,6 +312,16 @@ bns_status bns_profile_read(bns_ctx *ctx, double *ms_per_phase /* host [BNS_PHAS
 bns_status bns_probe_gather(const float *table, int64_t n_rows, int32_t d, const int32_t *idx,
                             int64_t n_idx, int32_t per_wave, float *out, void *stream);
 
+/* Instrumentation: the fp32 matrix instruction of the update (Eq. 2), v_mfma_f32_32x32x2_f32, with
+ * nothing else in the loop.  `blocks` workgroups of waves_per_block (1..16) wavefronts each issue
+ * iters * 8 * n_acc of them on n_acc (1, 2, 3, 4 or 6) independent accumulators per wavefront:
+ * 4096 * 8 * n_acc * iters * waves_per_block * blocks flops in all.  out dev f32[blocks] receives one
+ * checksum per workgroup (1024-thread workgroups leave 128 registers per wavefront, enough for
+ * every n_acc).  bench.py --mfma-regimes times it over wavefronts per SIMD x accumulators per
+ * wavefront: the issue rates the GEMM tile shapes were chosen by. */
+bns_status bns_probe_mfma(int32_t n_acc, int32_t waves_per_block, int32_t blocks, int32_t iters,
+                          float *out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ NOALLOC_MAX_HALO = 1 << 22
 EXPORTED = ["bns_workspace_bytes", "bns_create", "bns_destroy", "bns_last_error",
             "bns_sample_boundary", "bns_sample_boundary_noalloc", "bns_build_sampled_csr", "bns_gcn_layer_fwd",
             "bns_gcn_layer_bwd", "bns_train_step", "bns_graph_capture", "bns_graph_replay", "bns_set_dropout", "bns_layer_plan", "bns_adam_update", "bns_cache_input_aggregate", "bns_ws_view",
-            "bns_profile_enable", "bns_profile_read", "bns_probe_gather"]
+            "bns_profile_enable", "bns_profile_read", "bns_probe_gather", "bns_probe_mfma"]
 
 PHASES = ["sample", "build", "gather", "spmm_fwd", "gemm_fwd", "loss", "gemm_dw", "gemm_da",
           "spmm_bwd", "sgd", "spmm_long"]
@@ -106,6 +106,8 @@ def load_library():
     L.bns_profile_enable.argtypes = [vp, u32, i32]
     L.bns_probe_gather.restype = i32
     L.bns_probe_gather.argtypes = [vp, C.c_int64, i32, vp, C.c_int64, i32, vp, vp]
+    L.bns_probe_mfma.restype = i32
+    L.bns_probe_mfma.argtypes = [i32, i32, i32, i32, vp, vp]
     L.bns_profile_read.restype = i32
     L.bns_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i32)]
     _lib = L
@@ -151,6 +153,14 @@ def probe_gather(table, idx, per_wave, out):
                             _stream())
     if st != 0:
         raise BnsError(st, "bns_probe_gather")
+
+
+def probe_mfma(n_acc, waves_per_block, blocks, iters, out):
+    """bns_probe_mfma: a loop of fp32 matrix instructions on n_acc accumulators per wavefront."""
+    L = load_library()
+    st = L.bns_probe_mfma(n_acc, waves_per_block, blocks, iters, _ptr(out), _stream())
+    if st != 0:
+        raise BnsError(st, "bns_probe_mfma")
 
 
 class Context:

@@ -8,9 +8,10 @@
 // wavefronts (2 x 4), each 64 x 32 = two 32x32 accumulators; BN = 128 with an m-contiguous A (the
 // split-K weight gradient): 4 wavefronts (2 x 2), each 64 x 64; BN = 64 (chosen when it wastes
 // fewer padded columns, e.g. N = 172, 47, 41): 4 wavefronts (4 x 1), each 32 x 64.  Measured on
-// gfx950: four wavefronts per SIMD with four accumulators each issue matrix instructions at 79 %
-// of the peak rate even with nothing else in the loop, two accumulators each at 98 %; stand-alone
-// the 8-wavefront tile is 10 - 26 % faster than the 4-wavefront one, inside a training step 3 - 8 %
+// gfx950: the matrix pipe itself issues at 98 % of its peak whatever the number of wavefronts per
+// SIMD and of accumulators per wavefront (bns_probe_mfma), so a tile shape is judged by how well it
+// hides operand staging and barriers: stand-alone the 8-wavefront tile (six wavefronts per SIMD
+// instead of four) is 10 - 26 % faster than the 4-wavefront one, inside a training step 3 - 8 %
 // (the weight gradient, which streams both operands, lost 1 - 3 % and keeps four wavefronts).
 // Operand tiles of depth 16 are staged through LDS
 // in k-major order (As[k][m], Bs[k][n]) so that an MFMA operand read is one conflict-free row

@@ -49,7 +49,57 @@ probe_gather_kernel(const float *__restrict__ table, int32_t d, const int32_t *_
   if (b0 < n_idx && g == 0) reinterpret_cast<v4f *>(out + wave * d)[sl] = acc;
 }
 
+// The fp32 matrix instruction of the update (Eq. 2) with nothing else in the loop: every wavefront
+// issues iters x 8 x NACC v_mfma_f32_32x32x2_f32 on NACC independent accumulators.  How many of them a
+// SIMD issues per second depends on the wavefronts resident per SIMD and on NACC; the GEMM tiles
+// are shaped after what this measures.
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+template <int NACC>
+__global__ void __launch_bounds__(1024) probe_mfma_kernel(float *__restrict__ out, int iters, float a0, float b0) {
+  floatx16 acc[NACC];
+#pragma unroll
+  for (int i = 0; i < NACC; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  const float a = a0 + threadIdx.x * 1e-6f, b = b0;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int i = 0; i < NACC; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NACC; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  // one float per workgroup, so that the products are not optimised away
+  if (threadIdx.x == 0) out[blockIdx.x] = s;
+}
+
 }  // namespace bns
+
+extern "C" bns_status bns_probe_mfma(int32_t n_acc, int32_t waves_per_block, int32_t blocks, int32_t iters,
+                                     float *out, void *stream) {
+  using namespace bns;
+  if (!out || blocks < 1 || iters < 0 || waves_per_block < 1 || waves_per_block > 16) return BNS_EINVAL;
+  if (n_acc != 1 && n_acc != 2 && n_acc != 3 && n_acc != 4 && n_acc != 6) return BNS_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const unsigned threads = (unsigned)waves_per_block * kWave;
+  switch (n_acc) {
+    case 1: probe_mfma_kernel<1><<<(unsigned)blocks, threads, 0, s>>>(out, iters, 1.0f, 0.5f); break;
+    case 2: probe_mfma_kernel<2><<<(unsigned)blocks, threads, 0, s>>>(out, iters, 1.0f, 0.5f); break;
+    case 3: probe_mfma_kernel<3><<<(unsigned)blocks, threads, 0, s>>>(out, iters, 1.0f, 0.5f); break;
+    case 4: probe_mfma_kernel<4><<<(unsigned)blocks, threads, 0, s>>>(out, iters, 1.0f, 0.5f); break;
+    default: probe_mfma_kernel<6><<<(unsigned)blocks, threads, 0, s>>>(out, iters, 1.0f, 0.5f); break;
+  }
+  if (hipGetLastError() != hipSuccess) {
+    (void)hipGetLastError();
+    return BNS_EHIP;
+  }
+  return BNS_OK;
+}
 
 extern "C" bns_status bns_probe_gather(const float *table, int64_t n_rows, int32_t d, const int32_t *idx,
                                        int64_t n_idx, int32_t per_wave, float *out, void *stream) {

@@ -1,5 +1,7 @@
-"""bns_probe_gather, the bare access pattern of the aggregate used by bench.py as this machine's
-ceiling: every wavefront's row must be the plain sum of the table rows its indices name."""
+"""The two instrumentation kernels of the library.  bns_probe_gather, the bare access pattern of the
+aggregate used by bench.py as this machine's ceiling: every wavefront's row must be the plain sum of
+the table rows its indices name.  bns_probe_mfma, the bare matrix instruction of the update: its
+checksum must be what that many products add up to."""
 import numpy as np
 import pytest
 
@@ -40,3 +42,32 @@ def test_probe_rejects_bad_arguments():
         pkg.probe_gather(t, i, 4, o)
     with pytest.raises(pkg.BnsError):
         pkg.probe_gather(torch.zeros(8, 128, dtype=torch.float32, device=dev), i, 0, o)
+
+
+@pytest.mark.parametrize("n_acc,waves,iters", [(1, 4, 1), (4, 16, 3), (6, 8, 2), (2, 1, 5)])
+def test_mfma_probe_adds_up(n_acc, waves, iters):
+    """Every product adds sum_k A[i][k] B[k][j] with A[i][k] = 1 + 1e-6 * (lane i + 32 k) and B = 0.5 to
+    C[i][j]; thread 0 of a workgroup holds C[8 (r / 4) + r % 4][0] in register r and stores the sum
+    over its registers and accumulators."""
+    import torch
+    import paper_2203_10983_amd as pkg
+    dev = torch.device("cuda:0")
+    blocks = 5
+    out = torch.full((blocks + 1,), 7.0, dtype=torch.float32, device=dev)
+    pkg.probe_mfma(n_acc, waves, blocks, iters, out)
+    torch.cuda.synchronize()
+    a = lambda lane: 1.0 + 1e-6 * lane  # noqa: E731
+    per_product = sum(0.5 * (a(8 * (r // 4) + r % 4) + a(8 * (r // 4) + r % 4 + 32)) for r in range(16))
+    want = n_acc * 8 * iters * per_product
+    got = out.cpu().numpy()
+    assert np.allclose(got[:blocks], want, rtol=1e-5), (got, want)
+    assert got[blocks] == 7.0
+
+
+def test_mfma_probe_rejects_bad_arguments():
+    import torch
+    import paper_2203_10983_amd as pkg
+    out = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+    for args in ((5, 4, 1, 1), (4, 17, 1, 1), (4, 0, 1, 1), (4, 4, 0, 1), (4, 4, 1, -1)):
+        with pytest.raises(pkg.BnsError):
+            pkg.probe_mfma(*args, out)
