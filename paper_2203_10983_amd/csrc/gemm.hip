@@ -360,7 +360,9 @@ hipError_t gemm_nt(int32_t M, int32_t N, int32_t K, const float *A, const float 
 }
 
 // ---- split-K -----------------------------------------------------------------------------------
-constexpr int kSplitTargetBlocks = 768;
+// one round of resident workgroups: 256 compute units x 4 (LDS and registers allow four); measured
+// against 512, 768, 1536 and 2048 on workloads 2 - 5
+constexpr int kSplitTargetBlocks = 1024;
 constexpr int kReduceGroup = 16;
 
 static inline int splitk_chunk(int32_t M, int32_t N, int32_t K, int *splits_out) {
