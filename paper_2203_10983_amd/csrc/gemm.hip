@@ -10,8 +10,8 @@
 // fewer padded columns, e.g. N = 172, 47, 41): 4 wavefronts (4 x 1), each 32 x 64.  Measured on
 // gfx950: the matrix pipe itself issues at 98 % of its peak whatever the number of wavefronts per
 // SIMD and of accumulators per wavefront (bns_probe_mfma), so a tile shape is judged by how well it
-// hides operand staging and barriers: stand-alone the 8-wavefront tile (six wavefronts per SIMD
-// instead of four) is 10 - 26 % faster than the 4-wavefront one, inside a training step 3 - 8 %
+// hides operand staging and barriers: stand-alone the 8-wavefront tile (six to eight wavefronts per
+// SIMD instead of four) is 10 - 26 % faster than the 4-wavefront one, inside a training step 3 - 8 %
 // (the weight gradient, which streams both operands, lost 1 - 3 % and keeps four wavefronts).
 // Operand tiles of depth 16 are staged through LDS
 // in k-major order (As[k][m], Bs[k][n]) so that an MFMA operand read is one conflict-free row
@@ -145,7 +145,9 @@ __device__ __forceinline__ void store_ncontig(const FragN<COLS, NT> &f, float *_
 // product it is the concatenation along M (a_split a multiple of 128).  C2 (nullable): the result is the pair
 // [C | C2] split at column c_split (a multiple of the column tile), both with row stride ldc.
 template <int BN, bool A_KCONTIG, bool B_KCONTIG, int EPI>
-__global__ void __launch_bounds__(gemm_threads(BN, A_KCONTIG), 4)
+// The 8-wavefront tile is held to 64 registers, so that four workgroups (eight wavefronts per SIMD) fit a
+// compute unit: 1 - 2 % on the 512-wide products over three workgroups at 68 registers.
+__global__ void __launch_bounds__(gemm_threads(BN, A_KCONTIG), (BN == 128 && A_KCONTIG) ? 8 : 4)
 gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const float *__restrict__ B,
             int ldb, float *__restrict__ C, int ldc, int k_chunk, bool vec_a, bool vec_b,
             const float *__restrict__ mask_src, float alpha, const int *__restrict__ m_dev,
