@@ -105,23 +105,6 @@ __device__ __forceinline__ void load_ncontig(FragN<COLS, NT> &f, const float *__
     f.v[p] = load4_guarded(base + (size_t)k * ld + col0 + cq, vec_ok, valid);
   }
 }
-// The same tile moved from global memory straight into LDS (global_load_lds, 16 bytes per lane, a
-// wavefront instruction fills 1 KB = 256 / COLS consecutive tile rows): no registers, no LDS store
-// instructions.  Only for tiles that lie wholly inside the operand; completion is counted by vmcnt.
-template <int COLS, int NT>
-__device__ __forceinline__ void direct_ncontig(const float *__restrict__ base, int ld, int col0, int k0,
-                                               float *__restrict__ tile) {
-  constexpr int TPR = COLS / 4;    // lanes per tile row
-  constexpr int RPI = kWave / TPR; // tile rows per wavefront instruction
-  constexpr int PER_WAVE = (BK * COLS / 256) / (NT / kWave);  // 1 KB instructions per wavefront
-  const int lane = lane_id(), wid = threadIdx.x >> 6;
-#pragma unroll
-  for (int p = 0; p < PER_WAVE; ++p) {
-    const int inst = wid + p * (NT / kWave);
-    const int k = inst * RPI + lane / TPR, c = (lane % TPR) * 4;
-    __builtin_amdgcn_global_load_lds(base + (size_t)(k0 + k) * ld + col0 + c, tile + inst * 256, 16, 0, 0);
-  }
-}
 template <int COLS, int LD, int NT>
 __device__ __forceinline__ void store_ncontig(const FragN<COLS, NT> &f, float *__restrict__ tile) {
   constexpr int TPR = COLS / 4;
@@ -156,8 +139,7 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
   // Every tile is staged through registers.  (Filling the W tile of the forward product straight
   // into LDS with global_load_lds paid with four wavefronts per block, costs 3 % with eight; doing
   // it for both tiles of the transposed product was 25 % slower.)
-  constexpr bool kDirectB = false;
-  constexpr int LDA = BM + 4, LDB = kDirectB ? BN : BN + 4;
+  constexpr int LDA = BM + 4, LDB = BN + 4;
   constexpr int NT = gemm_threads(BN, A_KCONTIG);
   constexpr bool kEight = NT == 512;
   constexpr int TI = BN == 128 ? 2 : 1, TJ = kEight ? 1 : 2;  // 32 x 32 MFMA tiles per wavefront: TI x TJ
@@ -192,9 +174,7 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
   using FB = typename std::conditional<B_KCONTIG, FragK<BN, NT>, FragN<BN, NT>>::type;
   FA fa;
   FB fb;
-  bool reg_b = true;  // whether the B tile in flight sits in registers (else it goes straight to LDS)
-  auto load_tiles = [&](int k0, int buf) {
-    const bool full_k = k0 + BK <= k_end;
+  auto load_tiles = [&](int k0) {
     if constexpr (A_KCONTIG) {
       const float *Ab = A;
       int k0a = k0, kea = k_end;
@@ -213,28 +193,25 @@ gemm_kernel(int M, int N, int K, const float *__restrict__ A, int lda, const flo
     if constexpr (B_KCONTIG) {
       load_kcontig<BN, NT>(fb, B, ldb, bn0, N, k0, k_end, vec_b);
     } else {
-      reg_b = !(kDirectB && vec_b && full_k && bn0 + BN <= N);
-      if (reg_b) load_ncontig<BN, NT>(fb, B, ldb, bn0, N, k0, k_end, vec_b);
-      else direct_ncontig<BN, NT>(B, ldb, bn0, k0, Bs[buf]);
+      load_ncontig<BN, NT>(fb, B, ldb, bn0, N, k0, k_end, vec_b);
     }
   };
   auto store_tiles = [&](int buf) {
     if constexpr (A_KCONTIG) store_kcontig<BM, NT>(fa, As[buf]);
     else store_ncontig<BM, LDA, NT>(fa, As[buf]);
     if constexpr (B_KCONTIG) store_kcontig<BN, NT>(fb, Bs[buf]);
-    else if (reg_b) store_ncontig<BN, LDB, NT>(fb, Bs[buf]);
-    if (!reg_b) __builtin_amdgcn_s_waitcnt(0);  // the direct fill has landed
+    else store_ncontig<BN, LDB, NT>(fb, Bs[buf]);
   };
 
   const int nk = (k_end - k_begin + BK - 1) / BK;
   if (nk > 0) {
-    load_tiles(k_begin, 0);
+    load_tiles(k_begin);
     store_tiles(0);
   }
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < nk) load_tiles(k_begin + (kt + 1) * BK, buf ^ 1);
+    if (kt + 1 < nk) load_tiles(k_begin + (kt + 1) * BK);
     const float *as = As[buf] + wm + l32;
     const float *bs = Bs[buf] + wn + l32;
 #pragma unroll
